@@ -1,0 +1,93 @@
+"""numpy-facing wrapper of the C GEMM oracle (oracle/gemm_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  The definition implemented is the general matrix
+multiply of the paper's Section II, C = alpha*op(A)*op(B) + beta*C, batched with
+element strides, row-major, fp64 accumulation in increasing k.
+
+All arrays are flat or shaped numpy buffers; the caller states the logical
+problem (M, N, K, leading dimensions, strides) exactly as the C ABI of the
+product does, so the two can be driven from the same argument tuple.
+"""
+import ctypes
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+_i64 = ctypes.c_int64
+_f32 = ctypes.c_float
+_ptr = ctypes.c_void_p
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(_build.build())
+        head = [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _f32, _ptr, _i64, _ptr, _i64,
+                _f32, _ptr, _i64, _i64, _i64, _i64, _i64]
+        for name in ("oracle_gemm_f32", "oracle_gemm_bf16"):
+            f = getattr(L, name)
+            f.argtypes = head
+            f.restype = ctypes.c_int
+        for name in ("oracle_gemm_f32_entries", "oracle_gemm_bf16_entries"):
+            f = getattr(L, name)
+            f.argtypes = head + [_i64, _ptr, _ptr, _ptr, _ptr]
+            f.restype = ctypes.c_int
+        L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return lib().oracle_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    lib().oracle_set_num_threads(int(n))
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_ptr)
+
+
+def _check_in(a, dtype):
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("oracle operands must be C-contiguous %s buffers" % np.dtype(dtype).name)
+
+
+def gemm(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+         batch=1, strideA=0, strideB=0, strideC=0):
+    """In-place on C (float32 numpy buffer).  dtype is 'f32' or 'bf16' (A, B uint16 bits)."""
+    in_t = np.float32 if dtype == "f32" else np.uint16
+    _check_in(A, in_t)
+    _check_in(B, in_t)
+    _check_in(C, np.float32)
+    fn = lib().oracle_gemm_f32 if dtype == "f32" else lib().oracle_gemm_bf16
+    rc = fn(int(transA), int(transB), M, N, K, alpha, _p(A), lda, _p(B), ldb, beta, _p(C), ldc,
+            batch, strideA, strideB, strideC)
+    if rc != 0:
+        raise ValueError("oracle gemm: invalid arguments")
+    return C
+
+
+def gemm_entries(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc,
+                 batch, strideA, strideB, strideC, bb, ii, jj):
+    """Values of the listed output entries (b, i, j) by the same definition."""
+    in_t = np.float32 if dtype == "f32" else np.uint16
+    _check_in(A, in_t)
+    _check_in(B, in_t)
+    if C0 is not None:
+        _check_in(C0, np.float32)
+    bb = np.ascontiguousarray(bb, dtype=np.int64)
+    ii = np.ascontiguousarray(ii, dtype=np.int64)
+    jj = np.ascontiguousarray(jj, dtype=np.int64)
+    out = np.empty(bb.shape[0], dtype=np.float32)
+    fn = lib().oracle_gemm_f32_entries if dtype == "f32" else lib().oracle_gemm_bf16_entries
+    rc = fn(int(transA), int(transB), M, N, K, alpha, _p(A), lda, _p(B), ldb, beta, _p(C0), ldc,
+            batch, strideA, strideB, strideC, bb.shape[0], _p(bb), _p(ii), _p(jj), _p(out))
+    if rc != 0:
+        raise ValueError("oracle gemm_entries: invalid arguments")
+    return out
