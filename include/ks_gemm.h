@@ -1,0 +1,203 @@
+/*
+ * ks_gemm.h - C ABI of the tiled-GEMM kernel family with learned kernel selection.
+ *
+ * The library is the matrix-multiply case study of "Towards automated kernel
+ * selection in machine learning systems" (Lawson, 2020) rebuilt for one AMD
+ * MI355X (gfx950): a family of tiled GEMM kernels parameterised by work-group
+ * tile, wave/register tile and K-step (Section II), an offline tuner that turns
+ * brute-force timings into a pruned kept set with a decision-tree regression
+ * (Sections II-A, III, III-A) and a decision-tree runtime selector over the
+ * kept set (Section IV).
+ *
+ * Conventions shared by every entry point
+ *   - All matrices are ROW-MAJOR.  op(A) is M x K: transA == 0 means A is stored
+ *     M x K with row stride lda >= K; transA == 1 means A is stored K x M with
+ *     lda >= M.  op(B) is K x N: transB == 0 -> stored K x N, ldb >= N;
+ *     transB == 1 -> stored N x K, ldb >= K.  C is M x N with ldc >= N.
+ *     (A column-major caller uses C^T = op(B)^T op(A)^T: swap A<->B and M<->N.)
+ *   - Batch item b uses A + b*strideA, B + b*strideB, C + b*strideC (strides in
+ *     elements).  strideA / strideB may be 0 (the operand is shared).
+ *   - A, B, C, the workspace and every other pointer named "device" are DEVICE
+ *     pointers owned by the caller; the library never allocates, frees or keeps
+ *     them (except the registered workspace pointer).  Everything else is host
+ *     memory.  Calls are asynchronous on `stream` (a hipStream_t; NULL = the
+ *     default stream): buffers must stay alive until the stream has drained.
+ *   - beta == 0 means C is not read.  alpha == 0 has no special case.
+ *   - Every function returns a ks_status (0 = success, negative = error) unless
+ *     stated otherwise; on error nothing is launched and C is untouched.
+ *   - No entry point is a CPU fallback: without a HIP device the compute calls
+ *     fail with KS_ERR_LAUNCH.
+ */
+#ifndef KS_GEMM_H
+#define KS_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KS_OK = 0,
+    KS_ERR_INVALID_ARG = -1,   /* bad flag, negative size, short leading dimension, NULL operand,
+                                  overlapping batch items of C, id out of range */
+    KS_ERR_UNSUPPORTED = -2,   /* size beyond the 32-bit tile arithmetic of the kernels */
+    KS_ERR_LAUNCH = -3,        /* the HIP runtime refused the launch / no device */
+    KS_ERR_WORKSPACE = -4      /* a split-K kernel needs a larger registered workspace */
+} ks_status;
+
+typedef enum { KS_F32 = 0, KS_BF16 = 1 } ks_dtype;           /* type of A and B; C is fp32 */
+typedef enum { KS_CORE_FMA = 0, KS_CORE_MFMA16 = 1, KS_CORE_MFMA32 = 2 } ks_core;
+
+/* One member of the kernel family (Section II: work-group tile, per-work-item tile and
+ * accumulator step are the compile-time parameters of the paper's kernel). */
+typedef struct {
+    int32_t id;          /* dense, 0 .. ks_num_kernels(dtype)-1; frozen */
+    int32_t dtype;       /* ks_dtype */
+    int32_t core;        /* ks_core: per-lane FMA outer product, or MFMA with 16x16 / 32x32 fragments */
+    int32_t bm, bn, bk;  /* work-group tile rows, cols; K-step staged through LDS */
+    int32_t wm, wn;      /* wave tile (MFMA cores); equals tm x tn layout unit for the FMA core */
+    int32_t tm, tn;      /* per-lane register tile (FMA core) or fragments per wave (MFMA cores) */
+    int32_t threads;     /* work-group size */
+    int32_t split_k;     /* number of K partitions reduced through the workspace (1 = none) */
+    int32_t lds_bytes;   /* static LDS of the instantiation (both stages) */
+} ks_kernel_info_t;
+
+/* Node of a deployed decision tree (Section IV: nested integer comparisons).
+ * feature < 0 marks a leaf whose kernel id is `value`; otherwise go to `left` when
+ * features[feature] <= threshold, else to `right`. */
+typedef struct {
+    int32_t feature;
+    int32_t left, right;
+    int32_t value;
+    int64_t threshold;
+} ks_tree_node_t;
+
+/* Feature vector the trees see, computed from the call's sizes with integer arithmetic only:
+ * 0:M 1:N 2:K 3:batch 4:transA 5:transB  (the first KS_NUM_RAW_FEATURES)
+ * 6:M*N 7:M*N*K 8:min(M,N) 9:max(M,N)   (derived; saturating at INT64_MAX) */
+#define KS_NUM_RAW_FEATURES 6
+#define KS_NUM_FEATURES 10
+#define KS_MAX_TREE_NODES 4096
+
+/* ---------------------------------------------------------------- GEMM (Section II)
+ * C_b = alpha * op(A_b) * op(B_b) + beta * C_b for b in [0, batch).
+ * ks_gemm_* picks the kernel with ks_select (Section IV) and is bit-identical to
+ * ks_gemm_*_with_kernel(ks_select(...), ...).  A, B, C: device pointers.
+ * bf16 operands are raw bfloat16 bit patterns; accumulation and C are fp32.
+ * Degenerate sizes: M, N or batch == 0 -> success, nothing launched; K == 0 -> C = beta*C.
+ * Errors: KS_ERR_INVALID_ARG (see ks_status), KS_ERR_UNSUPPORTED when M, N or K >= 2^31 - 512,
+ * KS_ERR_WORKSPACE, KS_ERR_LAUNCH. */
+int ks_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                float beta, float *C, int64_t ldc,
+                int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+int ks_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                 float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                 float beta, float *C, int64_t ldc,
+                 int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+
+/* Tuner path (Section II-A brute force): the same call with the instantiation forced. */
+int ks_gemm_f32_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                            float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                            float beta, float *C, int64_t ldc,
+                            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                            void *stream);
+int ks_gemm_bf16_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                             float alpha, const uint16_t *A, int64_t lda, const uint16_t *B,
+                             int64_t ldb, float beta, float *C, int64_t ldc,
+                             int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                             void *stream);
+
+/* Brute-force timing of one (workload, instantiation) cell (Section II-A: runtime recorded over a
+ * number of iterations).  Runs `warmup` untimed launches, then `iters` samples; a sample is
+ * `reps` back-to-back launches bracketed by one pair of HIP events on `stream`.  Synchronises and
+ * writes the per-launch time of each sample (elapsed / reps) in milliseconds to
+ * ms_out[0 .. iters-1] (host).  dtype selects the f32 / bf16 entry point; A and B are device
+ * pointers of that type.  kernel_id < 0 times the selected kernel (ks_select).
+ * 1 <= iters <= 1024, reps >= 1, warmup >= 0. */
+int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                 float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                 float beta, float *C, int64_t ldc,
+                 int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                 void *stream, int warmup, int iters, int reps, float *ms_out);
+
+/* ---------------------------------------------------------------- registry (Section II)
+ * The enumerated family: 64 fp32 instantiations (the size of the paper's compiled set) and
+ * the bf16 set. */
+int ks_num_kernels(int dtype);                                   /* count, or negative status */
+int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out);   /* out: host */
+
+/* ---------------------------------------------------------------- selection (Section IV)
+ * Walks the deployed decision tree for `dtype` with integer comparisons only and returns the
+ * chosen kernel id (>= 0), or a negative status for a bad flag / negative size.  Pure, total
+ * over non-negative sizes, thread-safe, allocation-free, no device access. */
+int ks_select(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int transA, int transB);
+/* The integer features ks_select compares (out: host array of KS_NUM_FEATURES). */
+int ks_features(int64_t M, int64_t N, int64_t K, int64_t batch, int transA, int transB,
+                int64_t *out);
+/* Replace the deployed tree of `dtype` by a copy of nodes[0 .. n-1] (host; node 0 is the root).
+ * The tree is validated (child indices in range and acyclic by construction: children must have
+ * larger indices than their parent; leaf values must be kernel ids).  n == 0 restores the tree
+ * compiled into the library.  Not thread-safe against concurrent ks_select / ks_gemm calls. */
+int ks_set_selector(int dtype, const ks_tree_node_t *nodes, int n);
+/* Copy the deployed tree out (host).  Returns the node count, or a negative status if cap is
+ * too small. */
+int ks_get_selector(int dtype, ks_tree_node_t *nodes, int cap);
+
+/* ---------------------------------------------------------------- workspace
+ * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no
+ * atomics) need split_k * batch * M * N floats of scratch.  The caller registers one device
+ * buffer per process; NULL / 0 unregisters.  Kernels with split_k == 1 never touch it. */
+int ks_set_workspace(void *device_ptr, size_t bytes);
+size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N, int64_t batch);
+
+/* ---------------------------------------------------------------- offline tuner (host only)
+ * Sections II-A, III, III-A, IV on a timing table.  All arrays are host memory, row-major.
+ *   perf       rows x cols, performance of configuration c on workload s (any positive unit)
+ *   features   rows x n_features int64 feature vectors (ks_features layout, any prefix length)
+ * Trees are CART with integer thresholds floor(midpoint); "x <= t" goes left.  Ties: argmax ->
+ * lowest index; a split replaces the current best only if its gain is larger by a relative
+ * 1e-9; best-first priority ties -> earliest node.  Fully deterministic. */
+
+/* Section II-A: out[s][c] = perf[s][c] / max_c perf[s][c]. */
+int ks_tune_normalise(const double *perf, int rows, int cols, double *out);
+
+/* Section III (decision-tree pruning): fit a multi-output regression tree on `normalised`
+ * with at most max_leaves leaves (best-first), take each leaf's mean vector as a cluster
+ * representative and keep its best configuration.  kept_out (capacity max_leaves) receives the
+ * sorted distinct kept ids; returns how many, or a negative status.  If tree_out != NULL
+ * (capacity 2*max_leaves - 1 nodes) it receives the regression tree, leaf `value` = the
+ * representative's best configuration. */
+int ks_tune_prune_tree(const int64_t *features, int n_features, const double *normalised,
+                       int rows, int cols, int max_leaves, int min_samples_leaf,
+                       int32_t *kept_out, ks_tree_node_t *tree_out, int *tree_nodes_out);
+
+/* Section III-A score: geometric mean over rows of max_{c in kept} normalised[s][c]. */
+int ks_tune_achievable(const double *normalised, int rows, int cols, const int32_t *kept,
+                       int n_kept, double *score_out);
+
+/* Section IV: label each row with its fastest kept configuration and fit a Gini
+ * classification tree (depth-first, max_depth, min_samples_leaf).  row_weight may be NULL
+ * (every row counts 1, the paper's setting) or give one non-negative weight per row.
+ * Writes at most cap nodes to tree_out and returns the node count, or a negative status. */
+int ks_tune_fit_selector(const int64_t *features, int n_features, const double *perf, int rows,
+                         int cols, const int32_t *kept, int n_kept, int max_depth,
+                         int min_samples_leaf, const double *row_weight,
+                         ks_tree_node_t *tree_out, int cap);
+
+/* Walk `tree` for every row; chosen_out[s] = leaf value. */
+int ks_tune_predict(const ks_tree_node_t *tree, int n_nodes, const int64_t *features,
+                    int n_features, int rows, int32_t *chosen_out);
+
+/* Table I score: geometric mean over rows of normalised[s][chosen[s]]. */
+int ks_tune_selector_score(const double *normalised, int rows, int cols, const int32_t *chosen,
+                           double *score_out);
+
+const char *ks_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KS_GEMM_H */

@@ -1,0 +1,91 @@
+"""Build libks_gemm.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+
+    python -m paper_2003_06795_amd.build [--force] [-j N]
+
+The kernel family is compiled as shards of one source (-DKS_SHARD=n) so that the 64 fp32 and the
+bf16 instantiations build in parallel.  Objects go to _build/ (not tracked); the library lands
+next to this file.
+"""
+import argparse
+import concurrent.futures as cf
+import glob
+import os
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+OBJ = os.path.join(ROOT, "_build")
+LIB = os.path.join(PKG, "libks_gemm.so")
+SHARDS = 16
+
+HIPCC = os.environ.get("HIPCC", "hipcc")
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+CXX_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra"]
+
+
+def _deps():
+    return (glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(CSRC, "*.def"))
+            + glob.glob(os.path.join(CSRC, "*.inc")) + glob.glob(os.path.join(ROOT, "include", "*.h")))
+
+
+def _jobs():
+    jobs = []
+    for n in range(SHARDS):
+        for kind in ("f32", "bf16"):
+            src = os.path.join(CSRC, "instances_%s.hip" % kind)
+            jobs.append((src, os.path.join(OBJ, "inst_%s_%02d.o" % (kind, n)),
+                         [HIPCC] + HIP_FLAGS + ["-DKS_SHARD=%d" % n, "-c", src]))
+    src = os.path.join(CSRC, "dispatch.hip")
+    jobs.append((src, os.path.join(OBJ, "dispatch.o"), [HIPCC] + HIP_FLAGS + ["-c", src]))
+    for name in ("selector", "tune"):
+        src = os.path.join(CSRC, name + ".cpp")
+        jobs.append((src, os.path.join(OBJ, name + ".o"), ["g++"] + CXX_FLAGS + ["-c", src]))
+    return jobs
+
+
+def _compile(job):
+    src, obj, cmd = job
+    r = subprocess.run(cmd + ["-o", obj], capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    return obj, r.returncode, err
+
+
+def build(force=False, jobs=None, verbose=True):
+    os.makedirs(OBJ, exist_ok=True)
+    newest_dep = max(os.path.getmtime(p) for p in _deps())
+    todo, objs = [], []
+    for job in _jobs():
+        src, obj, _ = job
+        objs.append(obj)
+        stale = (force or not os.path.exists(obj)
+                 or os.path.getmtime(obj) < max(newest_dep, os.path.getmtime(src)))
+        if stale:
+            todo.append(job)
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    if todo:
+        if verbose:
+            print("[build] compiling %d objects with %d jobs" % (len(todo), jobs), flush=True)
+        with cf.ThreadPoolExecutor(max_workers=jobs) as ex:
+            for obj, rc, err in ex.map(_compile, todo):
+                if err.strip() and verbose:
+                    print(err, file=sys.stderr)
+                if rc != 0:
+                    raise RuntimeError("compile failed: %s\n%s" % (obj, err))
+    if todo or not os.path.exists(LIB):
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs, check=True)
+        os.replace(tmp, LIB)
+        if verbose:
+            print("[build] linked %s (%.1f MB)" % (LIB, os.path.getsize(LIB) / 1e6), flush=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--force", action="store_true")
+    ap.add_argument("-j", type=int, default=None)
+    a = ap.parse_args()
+    build(force=a.force, jobs=a.j)

@@ -1,0 +1,310 @@
+// Host side of the C ABI: argument validation, registry, launch geometry, timing helper.
+// Every compute step runs in the HIP kernels of this library; there is no CPU fallback.
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+
+#include "../../include/ks_gemm.h"
+#include "registry.hpp"
+
+namespace ks {
+
+#define KS_DECL(n)                              \
+    void register_f32_shard_##n(LaunchFn *);    \
+    void register_bf16_shard_##n(LaunchFn *);
+KS_DECL(0) KS_DECL(1) KS_DECL(2) KS_DECL(3) KS_DECL(4) KS_DECL(5) KS_DECL(6) KS_DECL(7)
+KS_DECL(8) KS_DECL(9) KS_DECL(10) KS_DECL(11) KS_DECL(12) KS_DECL(13) KS_DECL(14) KS_DECL(15)
+#undef KS_DECL
+
+namespace {
+
+constexpr int threads_of(int core, int bm, int bn, int p1, int p2) {
+    return core == KS_CORE_FMA ? (bm / p1) * (bn / p2) : 64 * (bm / p1) * (bn / p2);
+}
+
+constexpr int KS_CORE_OF_FMA = KS_CORE_FMA, KS_CORE_OF_MFMA16 = KS_CORE_MFMA16,
+              KS_CORE_OF_MFMA32 = KS_CORE_MFMA32;
+
+const InstanceDesc kF32[kNumF32] = {
+#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2)                                      \
+    {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), 1, \
+     2 * BK * ((BM + 4) + (BN + 4)) * 4},
+#include "instances.def"
+#undef KS_F32_INSTANCE
+};
+
+const InstanceDesc kBf16[kNumBf16] = {
+#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, SPLITK)                                   \
+    {id, (F) == 16 ? KS_CORE_MFMA16 : KS_CORE_MFMA32, BM, BN, BK, WM, WN, 64 * (BM / WM) * (BN / WN), \
+     SPLITK, 2 * BK * (BM + BN) * 2},
+#include "instances.def"
+#undef KS_BF16_INSTANCE
+};
+
+LaunchFn g_f32[kNumF32];
+LaunchFn g_bf16[kNumBf16];
+std::once_flag g_once;
+
+void init_tables() {
+    register_f32_shard_0(g_f32); register_f32_shard_1(g_f32); register_f32_shard_2(g_f32);
+    register_f32_shard_3(g_f32); register_f32_shard_4(g_f32); register_f32_shard_5(g_f32);
+    register_f32_shard_6(g_f32); register_f32_shard_7(g_f32); register_f32_shard_8(g_f32);
+    register_f32_shard_9(g_f32); register_f32_shard_10(g_f32); register_f32_shard_11(g_f32);
+    register_f32_shard_12(g_f32); register_f32_shard_13(g_f32); register_f32_shard_14(g_f32);
+    register_f32_shard_15(g_f32);
+    register_bf16_shard_0(g_bf16); register_bf16_shard_1(g_bf16); register_bf16_shard_2(g_bf16);
+    register_bf16_shard_3(g_bf16); register_bf16_shard_4(g_bf16); register_bf16_shard_5(g_bf16);
+    register_bf16_shard_6(g_bf16); register_bf16_shard_7(g_bf16); register_bf16_shard_8(g_bf16);
+    register_bf16_shard_9(g_bf16); register_bf16_shard_10(g_bf16); register_bf16_shard_11(g_bf16);
+    register_bf16_shard_12(g_bf16); register_bf16_shard_13(g_bf16); register_bf16_shard_14(g_bf16);
+    register_bf16_shard_15(g_bf16);
+}
+
+void *g_ws = nullptr;
+size_t g_wsBytes = 0;
+
+const InstanceDesc *desc_of(int dtype, int id) {
+    if (dtype == KS_F32) return (id >= 0 && id < kNumF32) ? &kF32[id] : nullptr;
+    if (dtype == KS_BF16) return (id >= 0 && id < kNumBf16) ? &kBf16[id] : nullptr;
+    return nullptr;
+}
+
+// C = beta * C for K == 0 (C is not read when beta == 0)
+__global__ void scale_c_kernel(float *C, long long ldc, long long strideC, int M, int N, int batch,
+                               float beta) {
+    const long long total = (long long)batch * M * N;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
+        float *c = C + b * strideC + (r / N) * ldc + (r % N);
+        *c = beta == 0.0f ? 0.0f : beta * *c;
+    }
+}
+
+// Split-K second pass: C = alpha * (ws[0] + ws[1] + ... in this fixed order) + beta * C
+__global__ void splitk_reduce_kernel(const float *ws, float *C, long long ldc, long long strideC, int M,
+                                     int N, int batch, int splitK, float alpha, float beta) {
+    const long long per = (long long)batch * M * N;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < per;
+         i += (long long)gridDim.x * blockDim.x) {
+        float acc = ws[i];
+        for (int s = 1; s < splitK; ++s) acc += ws[(long long)s * per + i];
+        const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
+        float *c = C + b * strideC + (r / N) * ldc + (r % N);
+        float v = alpha * acc;
+        if (beta != 0.0f) v = fmaf(beta, *c, v);
+        *c = v;
+    }
+}
+
+int validate(int transA, int transB, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+             const void *B, int64_t ldb, const float *C, int64_t ldc, int64_t batch,
+             int64_t strideC) {
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return KS_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || batch < 0) return KS_ERR_INVALID_ARG;
+    const int64_t lim = 2147483647LL - 512;
+    if (M >= lim || N >= lim || K >= lim || batch >= lim) return KS_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0 || batch == 0) return KS_OK;
+    if (!C || ldc < N) return KS_ERR_INVALID_ARG;
+    if (K > 0) {
+        if (!A || !B) return KS_ERR_INVALID_ARG;
+        if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return KS_ERR_INVALID_ARG;
+    }
+    if (batch > 1) {
+        const int64_t span = (M - 1) * ldc + N;       // elements one item of C covers
+        const int64_t s = strideC < 0 ? -strideC : strideC;
+        if (s < span) return KS_ERR_INVALID_ARG;
+    }
+    return KS_OK;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+        const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
+        int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream) {
+    const InstanceDesc *d = desc_of(dtype, id);
+    if (!d) return KS_ERR_INVALID_ARG;
+    const int rc = validate(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, batch, strideC);
+    if (rc != KS_OK) return rc;
+    if (M == 0 || N == 0 || batch == 0) return KS_OK;
+    std::call_once(g_once, init_tables);
+
+    if (K == 0) {
+        const long long total = (long long)batch * M * N;
+        const int grid = (int)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
+        hipLaunchKernelGGL(scale_c_kernel, dim3(grid), dim3(256), 0, stream, C, (long long)ldc,
+                           (long long)strideC, (int)M, (int)N, (int)batch, beta);
+        return hipGetLastError() == hipSuccess ? KS_OK : KS_ERR_LAUNCH;
+    }
+
+    GemmParams p;
+    p.A = A; p.B = B; p.C = C; p.ws = nullptr;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.strideA = strideA; p.strideB = strideB; p.strideC = strideC;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = (int)batch;
+    p.tilesM = (int)((M + d->bm - 1) / d->bm);
+    p.tilesN = (int)((N + d->bn - 1) / d->bn);
+    p.splitK = d->splitK;
+    const int64_t kTiles = (K + d->bk - 1) / d->bk;
+    p.kChunk = (int)(((kTiles + p.splitK - 1) / p.splitK) * d->bk);
+    p.alpha = alpha; p.beta = beta;
+
+    const int64_t grid64 = (int64_t)p.tilesM * p.tilesN * batch * p.splitK;
+    if (grid64 > 2147483647LL) return KS_ERR_UNSUPPORTED;
+
+    if (p.splitK > 1) {
+        const size_t need = (size_t)p.splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+        if (!g_ws || g_wsBytes < need) return KS_ERR_WORKSPACE;
+        p.ws = static_cast<float *>(g_ws);
+    }
+
+    // contiguous direction: A is K-contiguous when not transposed, B when transposed
+    const bool akc = transA == 0, bkc = transB == 1;
+    const int w = dtype == KS_F32 ? 4 : 8;            // elements per 16-byte access
+    const int64_t extA = akc ? K : M, extB = bkc ? K : N;
+    const bool vec = aligned(A, 16) && aligned(B, 16) && lda % w == 0 && ldb % w == 0 &&
+                     extA % w == 0 && extB % w == 0 &&
+                     (batch == 1 || (strideA % w == 0 && strideB % w == 0));
+    const int variant = (akc ? 4 : 0) + (bkc ? 2 : 0) + (vec ? 1 : 0);
+
+    (dtype == KS_F32 ? g_f32[id] : g_bf16[id])(p, (int)grid64, variant, stream);
+    if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
+
+    if (p.splitK > 1) {
+        const long long total = (long long)batch * M * N;
+        const int grid = (int)((total + 255) / 256 < 1048576 ? (total + 255) / 256 : 1048576);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(grid), dim3(256), 0, stream, p.ws, C,
+                           (long long)ldc, (long long)strideC, (int)M, (int)N, (int)batch, p.splitK,
+                           alpha, beta);
+        if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
+    }
+    return KS_OK;
+}
+
+}  // namespace
+}  // namespace ks
+
+using namespace ks;
+
+extern "C" int ks_num_kernels(int dtype) {
+    if (dtype == KS_F32) return kNumF32;
+    if (dtype == KS_BF16) return kNumBf16;
+    return KS_ERR_INVALID_ARG;
+}
+
+extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
+    const InstanceDesc *d = desc_of(dtype, kernel_id);
+    if (!d || !out) return KS_ERR_INVALID_ARG;
+    out->id = d->id;
+    out->dtype = dtype;
+    out->core = d->core;
+    out->bm = d->bm; out->bn = d->bn; out->bk = d->bk;
+    const int frag = d->core == KS_CORE_MFMA16 ? 16 : 32;
+    if (d->core == KS_CORE_FMA) {
+        out->wm = d->p1; out->wn = d->p2; out->tm = d->p1; out->tn = d->p2;
+    } else {
+        out->wm = d->p1; out->wn = d->p2; out->tm = d->p1 / frag; out->tn = d->p2 / frag;
+    }
+    out->threads = d->threads;
+    out->split_k = d->splitK;
+    out->lds_bytes = d->ldsBytes;
+    return KS_OK;
+}
+
+extern "C" int ks_set_workspace(void *device_ptr, size_t bytes) {
+    if (device_ptr == nullptr || bytes == 0) {
+        g_ws = nullptr;
+        g_wsBytes = 0;
+        return KS_OK;
+    }
+    g_ws = device_ptr;
+    g_wsBytes = bytes;
+    return KS_OK;
+}
+
+extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N,
+                                            int64_t batch) {
+    const InstanceDesc *d = desc_of(dtype, kernel_id);
+    if (!d || d->splitK <= 1 || M <= 0 || N <= 0 || batch <= 0) return 0;
+    return (size_t)d->splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+}
+
+#define KS_GEMM_PASS                                                                            \
+    transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batch, strideA, strideB, strideC, \
+        static_cast<hipStream_t>(stream)
+
+static int select_checked(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int tA, int tB) {
+    return ks_select(dtype, M, N, K, batch, tA, tB);
+}
+
+extern "C" int ks_gemm_f32_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                                       int64_t K, float alpha, const float *A, int64_t lda,
+                                       const float *B, int64_t ldb, float beta, float *C, int64_t ldc,
+                                       int64_t batch, int64_t strideA, int64_t strideB,
+                                       int64_t strideC, void *stream) {
+    return run(KS_F32, kernel_id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_gemm_bf16_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                                        int64_t K, float alpha, const uint16_t *A, int64_t lda,
+                                        const uint16_t *B, int64_t ldb, float beta, float *C,
+                                        int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,
+                                        int64_t strideC, void *stream) {
+    return run(KS_BF16, kernel_id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+                           const float *A, int64_t lda, const float *B, int64_t ldb, float beta,
+                           float *C, int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,
+                           int64_t strideC, void *stream) {
+    const int id = select_checked(KS_F32, M, N, K, batch, transA, transB);
+    if (id < 0) return id;
+    return run(KS_F32, id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+                            const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, float beta,
+                            float *C, int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,
+                            int64_t strideC, void *stream) {
+    const int id = select_checked(KS_BF16, M, N, K, batch, transA, transB);
+    if (id < 0) return id;
+    return run(KS_BF16, id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                            int64_t K, float alpha, const void *A, int64_t lda, const void *B,
+                            int64_t ldb, float beta, float *C, int64_t ldc, int64_t batch,
+                            int64_t strideA, int64_t strideB, int64_t strideC, void *stream,
+                            int warmup, int iters, int reps, float *ms_out) {
+    if (dtype != KS_F32 && dtype != KS_BF16) return KS_ERR_INVALID_ARG;
+    if (iters < 1 || iters > 1024 || reps < 1 || warmup < 0 || !ms_out) return KS_ERR_INVALID_ARG;
+    if (kernel_id < 0) {
+        kernel_id = ks_select(dtype, M, N, K, batch, transA, transB);
+        if (kernel_id < 0) return kernel_id;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the first call also proves the arguments: nothing is timed if it fails
+    int rc = run(dtype, kernel_id, KS_GEMM_PASS);
+    if (rc != KS_OK) return rc;
+    for (int i = 1; i < warmup; ++i) run(dtype, kernel_id, KS_GEMM_PASS);
+    static hipEvent_t ev[2 * 1024];
+    static int evCount = 0;
+    while (evCount < 2 * iters) {
+        if (hipEventCreate(&ev[evCount]) != hipSuccess) return KS_ERR_LAUNCH;
+        ++evCount;
+    }
+    for (int i = 0; i < iters; ++i) {
+        hipEventRecord(ev[2 * i], s);
+        for (int r = 0; r < reps; ++r) rc |= run(dtype, kernel_id, KS_GEMM_PASS);
+        hipEventRecord(ev[2 * i + 1], s);
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return KS_ERR_LAUNCH;
+    if (rc != KS_OK) return KS_ERR_LAUNCH;
+    for (int i = 0; i < iters; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess) return KS_ERR_LAUNCH;
+        ms_out[i] = ms / (float)reps;
+    }
+    return KS_OK;
+}

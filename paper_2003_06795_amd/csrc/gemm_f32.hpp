@@ -1,0 +1,261 @@
+// fp32 members of the tiled GEMM family (paper Section II).
+//
+// One kernel template; an instantiation fixes
+//   BM x BN   work-group tile of C, staged operand tiles live in LDS (double buffered)
+//   BK        K-step per stage (the paper's accumulator step, at work-group granularity)
+//   CORE      inner-product engine:
+//               FMA     each lane owns a TM x TN register tile and does outer-product FMAs;
+//                       work-group = (BM/TM) x (BN/TN) lanes  (the paper's per-work-item tile)
+//               MFMA16  each wave owns WM x WN built from 16x16x4 fp32 MFMA fragments
+//               MFMA32  each wave owns WM x WN built from 32x32x2 fp32 MFMA fragments
+//   P1 x P2   TM x TN for FMA, WM x WN for the MFMA cores
+//   AKC/BKC   whether op(A)/op(B) is K-contiguous in memory (A: transA == 0, B: transB == 1);
+//             decides the coalescing direction of the global loads
+//   VEC       operands are 16-byte aligned with leading dimensions and contiguous extents that
+//             are multiples of 4, so global accesses are float4; otherwise scalar.  Both forms
+//             predicate every access against the matrix edges and zero-fill.
+//
+// LDS layout (both operands): tile[k][m or n] with the row padded by 4 floats.  All cores read
+// "one k, many m/n", so rows of consecutive m/n are conflict-free for them.
+#pragma once
+#include "ks_common.hpp"
+
+namespace ks {
+
+enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2 };
+
+template <int CORE, int BM, int BN, int P1, int P2>
+struct F32Shape {
+    static constexpr int threads =
+        CORE == CORE_FMA ? (BM / P1) * (BN / P2) : 64 * (BM / P1) * (BN / P2);
+    static constexpr int frag = CORE == CORE_MFMA16 ? 16 : 32;
+};
+
+// ---- global -> registers -> LDS staging of one ROWS x BK operand tile ------------------------
+// KC:  memory is [row][k] (k contiguous);  !KC: memory is [k][row] (row contiguous).
+// Units are float4 (VEC) or single floats walked so that consecutive lanes touch consecutive
+// addresses.  INNER = units along the contiguous direction, OUTER = the other direction.
+template <int ROWS, int BK, int NT, bool KC, bool VEC>
+struct TileLoader {
+    static constexpr int W = VEC ? 4 : 1;
+    static constexpr int INNER = (KC ? BK : ROWS) / W;
+    static constexpr int OUTER = KC ? ROWS : BK;
+    static constexpr int UNITS = INNER * OUTER;
+    static constexpr int ITERS = (UNITS + NT - 1) / NT;
+    static constexpr int LDS_LD = ROWS + 4;
+    static_assert((INNER <= NT && NT % INNER == 0) || (INNER > NT && INNER % NT == 0), "walk");
+
+    float reg[ITERS][W];
+
+    __device__ __forceinline__ static void unit(int tid, int it, int &inner, int &outer) {
+        if constexpr (INNER <= NT) {
+            inner = tid % INNER;
+            outer = tid / INNER + it * (NT / INNER);
+        } else {
+            inner = tid + (it % (INNER / NT)) * NT;
+            outer = it / (INNER / NT);
+        }
+    }
+
+    // rowLimit: number of valid rows from row0 on; k runs from k0, valid while < kEnd.
+    __device__ __forceinline__ void load(const float *base, long long ld, int row0, int rowLimit,
+                                         int k0, int kEnd, int tid) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            int inner, outer;
+            unit(tid, it, inner, outer);
+            const int r = KC ? outer : inner * W;
+            const int k = KC ? inner * W : outer;
+            const bool ok = (UNITS % NT == 0 || outer < OUTER) && (row0 + r < rowLimit) && (k0 + k < kEnd);
+            const float *src = KC ? base + (long long)(row0 + r) * ld + (k0 + k)
+                                  : base + (long long)(k0 + k) * ld + (row0 + r);
+            if constexpr (VEC) {
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};
+                if (ok) v = *reinterpret_cast<const floatx4 *>(src);
+                reg[it][0] = v.x; reg[it][1] = v.y; reg[it][2] = v.z; reg[it][3] = v.w;
+            } else {
+                reg[it][0] = ok ? *src : 0.f;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store(float *lds, int tid) const {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            int inner, outer;
+            unit(tid, it, inner, outer);
+            if (UNITS % NT != 0 && outer >= OUTER) continue;
+            const int r = KC ? outer : inner * W;
+            const int k = KC ? inner * W : outer;
+            if constexpr (VEC && !KC) {
+                floatx4 v = {reg[it][0], reg[it][1], reg[it][2], reg[it][3]};
+                *reinterpret_cast<floatx4 *>(lds + k * LDS_LD + r) = v;
+            } else if constexpr (VEC) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) lds[(k + j) * LDS_LD + r] = reg[it][j];
+            } else {
+                lds[k * LDS_LD + r] = reg[it][0];
+            }
+        }
+    }
+};
+
+template <int CORE, int BM, int BN, int BK, int P1, int P2, bool AKC, bool BKC, bool VEC>
+__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gemm_f32_kernel(
+    const GemmParams p) {
+    using Shape = F32Shape<CORE, BM, BN, P1, P2>;
+    constexpr int NT = Shape::threads;
+    constexpr int LDA = BM + 4, LDB = BN + 4;
+    __shared__ __attribute__((aligned(16))) float As[2][BK * LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
+
+    const int tid = threadIdx.x;
+    const TileCoord tc = tile_of_block(p);
+    const int row0 = tc.tm * BM, col0 = tc.tn * BN;
+    const float *Ab = static_cast<const float *>(p.A) + (long long)tc.batch * p.strideA;
+    const float *Bb = static_cast<const float *>(p.B) + (long long)tc.batch * p.strideB;
+    float *Cb = p.C + (long long)tc.batch * p.strideC;
+    const int kBegin = tc.split * p.kChunk;
+    const int kEnd = min(p.K, kBegin + p.kChunk);
+    const int nk = (kEnd - kBegin + BK - 1) / BK;
+
+    TileLoader<BM, BK, NT, AKC, VEC> la;
+    TileLoader<BN, BK, NT, BKC, VEC> lb;
+
+    // accumulators
+    constexpr int FR = Shape::frag;
+    constexpr int FM = CORE == CORE_FMA ? 1 : P1 / FR, FN = CORE == CORE_FMA ? 1 : P2 / FR;
+    float accF[CORE == CORE_FMA ? P1 : 1][CORE == CORE_FMA ? P2 : 1];
+    floatx4 acc16[CORE == CORE_MFMA16 ? FM : 1][CORE == CORE_MFMA16 ? FN : 1];
+    floatx16 acc32[CORE == CORE_MFMA32 ? FM : 1][CORE == CORE_MFMA32 ? FN : 1];
+    if constexpr (CORE == CORE_FMA) {
+#pragma unroll
+        for (int i = 0; i < P1; ++i)
+#pragma unroll
+            for (int j = 0; j < P2; ++j) accF[i][j] = 0.f;
+    } else if constexpr (CORE == CORE_MFMA16) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc16[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    } else {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+    }
+
+    // lane -> sub-tile origin inside the work-group tile
+    const int lane = tid & 63, wave = tid >> 6;
+    int subM, subN;
+    if constexpr (CORE == CORE_FMA) {
+        subM = (tid / (BN / P2)) * P1;
+        subN = (tid % (BN / P2)) * P2;
+    } else {
+        subM = (wave / (BN / P2)) * P1;
+        subN = (wave % (BN / P2)) * P2;
+    }
+
+    if (nk > 0) {
+        la.load(Ab, p.lda, row0, p.M, kBegin, kEnd, tid);
+        lb.load(Bb, p.ldb, col0, p.N, kBegin, kEnd, tid);
+        la.store(As[0], tid);
+        lb.store(Bs[0], tid);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) {
+            const int k0 = kBegin + (kt + 1) * BK;
+            la.load(Ab, p.lda, row0, p.M, k0, kEnd, tid);
+            lb.load(Bb, p.ldb, col0, p.N, k0, kEnd, tid);
+        }
+        const float *as = As[cur], *bs = Bs[cur];
+        if constexpr (CORE == CORE_FMA) {
+#pragma unroll
+            for (int kk = 0; kk < BK; ++kk) {
+                float a[P1], b[P2];
+#pragma unroll
+                for (int i = 0; i < P1; ++i) a[i] = as[kk * LDA + subM + i];
+#pragma unroll
+                for (int j = 0; j < P2; ++j) b[j] = bs[kk * LDB + subN + j];
+#pragma unroll
+                for (int i = 0; i < P1; ++i)
+#pragma unroll
+                    for (int j = 0; j < P2; ++j) accF[i][j] = fmaf(a[i], b[j], accF[i][j]);
+            }
+        } else if constexpr (CORE == CORE_MFMA16) {
+            // 16x16x4: lane l feeds A[l%16][l/16] and B[l/16][l%16]
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 4) {
+                const int kr = kk + (lane >> 4);
+                float a[FM], b[FN];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) a[i] = as[kr * LDA + subM + i * 16 + (lane & 15)];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) b[j] = bs[kr * LDB + subN + j * 16 + (lane & 15)];
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[j], acc16[i][j], 0, 0, 0);
+            }
+        } else {
+            // 32x32x2: lane l feeds A[l%32][l/32] and B[l/32][l%32]
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 2) {
+                const int kr = kk + (lane >> 5);
+                float a[FM], b[FN];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) a[i] = as[kr * LDA + subM + i * 32 + (lane & 31)];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) b[j] = bs[kr * LDB + subN + j * 32 + (lane & 31)];
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc32[i][j], 0, 0, 0);
+            }
+        }
+        if (more) {
+            la.store(As[cur ^ 1], tid);
+            lb.store(Bs[cur ^ 1], tid);
+        }
+        __syncthreads();
+    }
+
+    // epilogue
+    if constexpr (CORE == CORE_FMA) {
+#pragma unroll
+        for (int i = 0; i < P1; ++i)
+#pragma unroll
+            for (int j = 0; j < P2; ++j)
+                store_entry(p, tc, Cb, row0 + subM + i, col0 + subN + j, accF[i][j]);
+    } else if constexpr (CORE == CORE_MFMA16) {
+        // accumulator register e of lane l holds C[4*(l/16) + e][l%16]
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    store_entry(p, tc, Cb, row0 + subM + i * 16 + 4 * (lane >> 4) + e,
+                                col0 + subN + j * 16 + (lane & 15), acc16[i][j][e]);
+    } else {
+        // accumulator register e of lane l holds C[8*(e/4) + 4*(l/32) + e%4][l%32]
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    store_entry(p, tc, Cb, row0 + subM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3),
+                                col0 + subN + j * 32 + (lane & 31), acc32[i][j][e]);
+    }
+}
+
+}  // namespace ks

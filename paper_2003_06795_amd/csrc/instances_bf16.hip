@@ -1,0 +1,41 @@
+// One shard of the bf16 instantiations (see instances_f32.hip for the sharding scheme).
+#include "gemm_bf16.hpp"
+#include "registry.hpp"
+
+#ifndef KS_SHARD
+#error "compile with -DKS_SHARD=<n>"
+#endif
+#define KS_CAT2(a, b) a##b
+#define KS_CAT(a, b) KS_CAT2(a, b)
+
+namespace ks {
+
+template <int F, int BM, int BN, int BK, int WM, int WN>
+static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t s) {
+    constexpr int NT = 64 * (BM / WM) * (BN / WN);
+    const dim3 g((unsigned)grid), b(NT);
+#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, A, B, V>), g, b, 0, s, p)
+    switch (variant) {
+        case 0: KS_V(false, false, false); break;
+        case 1: KS_V(false, false, true); break;
+        case 2: KS_V(false, true, false); break;
+        case 3: KS_V(false, true, true); break;
+        case 4: KS_V(true, false, false); break;
+        case 5: KS_V(true, false, true); break;
+        case 6: KS_V(true, true, false); break;
+        default: KS_V(true, true, true); break;
+    }
+#undef KS_V
+}
+
+template <int SHARD>
+static void fill(LaunchFn *table) {
+#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, SPLITK) \
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16<F, BM, BN, BK, WM, WN>;
+#include "instances.def"
+#undef KS_BF16_INSTANCE
+}
+
+void KS_CAT(register_bf16_shard_, KS_SHARD)(LaunchFn *table) { fill<KS_SHARD>(table); }
+
+}  // namespace ks

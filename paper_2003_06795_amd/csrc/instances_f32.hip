@@ -1,0 +1,42 @@
+// One shard of the fp32 instantiations: compiled KS_NSHARDS times with -DKS_SHARD=0..KS_NSHARDS-1
+// so the family builds in parallel.  Each shard fills its ids of the launch table.
+#include "gemm_f32.hpp"
+#include "registry.hpp"
+
+#ifndef KS_SHARD
+#error "compile with -DKS_SHARD=<n>"
+#endif
+#define KS_CAT2(a, b) a##b
+#define KS_CAT(a, b) KS_CAT2(a, b)
+
+namespace ks {
+
+template <int CORE, int BM, int BN, int BK, int P1, int P2>
+static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s) {
+    constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads;
+    const dim3 g((unsigned)grid), b(NT);
+#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, A, B, V>), g, b, 0, s, p)
+    switch (variant) {
+        case 0: KS_V(false, false, false); break;
+        case 1: KS_V(false, false, true); break;
+        case 2: KS_V(false, true, false); break;
+        case 3: KS_V(false, true, true); break;
+        case 4: KS_V(true, false, false); break;
+        case 5: KS_V(true, false, true); break;
+        case 6: KS_V(true, true, false); break;
+        default: KS_V(true, true, true); break;
+    }
+#undef KS_V
+}
+
+template <int SHARD>
+static void fill(LaunchFn *table) {
+#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2) \
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2>;
+#include "instances.def"
+#undef KS_F32_INSTANCE
+}
+
+void KS_CAT(register_f32_shard_, KS_SHARD)(LaunchFn *table) { fill<KS_SHARD>(table); }
+
+}  // namespace ks

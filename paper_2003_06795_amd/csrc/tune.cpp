@@ -1,0 +1,296 @@
+// Offline tuner, host only (paper Sections II-A, III, III-A, IV): normalise a timing table,
+// prune the family with a leaf-limited multi-output regression tree, score the kept set,
+// fit the decision-tree selector and score it.  Plain C++; deterministic.
+//
+// Both trees are CART over integer features.  A candidate split "x[f] <= t" uses
+// t = floor(midpoint) of two consecutive distinct values.  With per-row target vectors y_s
+// (normalised performance for the regression tree, weighted one-hot labels for the Gini
+// classifier) and row weights w_s, the impurity a split removes is
+//     gain = |S_L|^2 / W_L + |S_R|^2 / W_R - |S|^2 / W,     S = sum_s w_s y_s,  W = sum_s w_s
+// which is the drop in summed squared error, and for one-hot targets the drop in n * Gini.
+#include "../../include/ks_gemm.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+namespace {
+
+constexpr double kRelEps = 1e-9;   // a candidate must beat the incumbent by this relative margin
+constexpr double kMinGain = 1e-12;
+
+inline bool better(double gain, double best) { return gain > best + kRelEps * std::fabs(best); }
+
+struct Split {
+    bool ok = false;
+    double gain = 0.0;
+    int feature = -1;
+    int64_t threshold = 0;
+};
+
+struct Table {
+    const int64_t *X;
+    int nf;
+    const double *Y;      // rows x cols targets
+    int cols;
+    const double *w;      // per-row weight or nullptr
+};
+
+double weight_of(const Table &t, int row) { return t.w ? t.w[row] : 1.0; }
+
+Split best_split(const Table &t, const std::vector<int> &rows, int minLeaf) {
+    Split best;
+    const int n = (int)rows.size();
+    if (n < 2 * minLeaf || n < 2) return best;
+    std::vector<double> tot(t.cols, 0.0), left(t.cols);
+    double W = 0.0;
+    for (int r : rows) {
+        const double w = weight_of(t, r);
+        W += w;
+        for (int c = 0; c < t.cols; ++c) tot[c] += w * t.Y[(size_t)r * t.cols + c];
+    }
+    if (!(W > 0.0)) return best;
+    double base = 0.0;
+    for (int c = 0; c < t.cols; ++c) base += tot[c] * tot[c];
+    base /= W;
+    std::vector<int> order(rows);
+    for (int f = 0; f < t.nf; ++f) {
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+            const int64_t xa = t.X[(size_t)a * t.nf + f], xb = t.X[(size_t)b * t.nf + f];
+            return xa != xb ? xa < xb : a < b;
+        });
+        std::fill(left.begin(), left.end(), 0.0);
+        double WL = 0.0;
+        for (int i = 0; i + 1 < n; ++i) {
+            const int r = order[i];
+            const double w = weight_of(t, r);
+            WL += w;
+            for (int c = 0; c < t.cols; ++c) left[c] += w * t.Y[(size_t)r * t.cols + c];
+            const int64_t xa = t.X[(size_t)r * t.nf + f], xb = t.X[(size_t)order[i + 1] * t.nf + f];
+            if (xa == xb) continue;
+            if (i + 1 < minLeaf || n - (i + 1) < minLeaf) continue;
+            const double WR = W - WL;
+            if (!(WL > 0.0) || !(WR > 0.0)) continue;
+            double sl = 0.0, sr = 0.0;
+            for (int c = 0; c < t.cols; ++c) {
+                const double l = left[c], r2 = tot[c] - left[c];
+                sl += l * l;
+                sr += r2 * r2;
+            }
+            const double gain = sl / WL + sr / WR - base;
+            if (gain <= kMinGain) continue;
+            if (!best.ok || better(gain, best.gain)) {
+                best.ok = true;
+                best.gain = gain;
+                best.feature = f;
+                // floor of the midpoint, also for negative values
+                const int64_t sum = xa + xb;
+                best.threshold = sum >= 0 ? sum / 2 : -((-sum + 1) / 2);
+            }
+        }
+    }
+    return best;
+}
+
+void partition(const Table &t, const std::vector<int> &rows, const Split &s, std::vector<int> &l,
+               std::vector<int> &r) {
+    for (int row : rows) (t.X[(size_t)row * t.nf + s.feature] <= s.threshold ? l : r).push_back(row);
+}
+
+int argmax_mean(const Table &t, const std::vector<int> &rows) {
+    int best = 0;
+    double bestV = -1.0;
+    for (int c = 0; c < t.cols; ++c) {
+        double s = 0.0;
+        for (int r : rows) s += t.Y[(size_t)r * t.cols + c];
+        s /= (double)rows.size();
+        if (s > bestV) { bestV = s; best = c; }
+    }
+    return best;
+}
+
+struct Grow {
+    const Table &t;
+    const std::vector<int> &label;     // class index per row
+    const std::vector<int32_t> &classId;
+    int maxDepth, minLeaf, cap;
+    std::vector<ks_tree_node_t> nodes;
+    bool overflow = false;
+
+    int grow(const std::vector<int> &rows, int depth) {
+        if ((int)nodes.size() >= cap) { overflow = true; return -1; }
+        const int me = (int)nodes.size();
+        nodes.push_back(ks_tree_node_t{-1, -1, -1, 0, 0});
+        // majority by weight, lowest kernel id on ties (classId is ascending)
+        std::vector<double> mass(classId.size(), 0.0);
+        bool pure = true;
+        for (int r : rows) {
+            mass[label[r]] += weight_of(t, r);
+            pure = pure && label[r] == label[rows[0]];
+        }
+        int top = 0;
+        for (size_t k = 1; k < mass.size(); ++k) if (mass[k] > mass[top]) top = (int)k;
+        nodes[me].value = classId[top];
+        if (pure || depth >= maxDepth) return me;
+        const Split s = best_split(t, rows, minLeaf);
+        if (!s.ok) return me;
+        std::vector<int> l, r;
+        partition(t, rows, s, l, r);
+        const int li = grow(l, depth + 1);
+        const int ri = overflow ? -1 : grow(r, depth + 1);
+        if (overflow) return me;
+        nodes[me].feature = s.feature;
+        nodes[me].threshold = s.threshold;
+        nodes[me].left = li;
+        nodes[me].right = ri;
+        return me;
+    }
+};
+
+}  // namespace
+
+extern "C" int ks_tune_normalise(const double *perf, int rows, int cols, double *out) {
+    if (!perf || !out || rows < 0 || cols <= 0) return KS_ERR_INVALID_ARG;
+    for (int s = 0; s < rows; ++s) {
+        double m = perf[(size_t)s * cols];
+        for (int c = 1; c < cols; ++c) m = std::max(m, perf[(size_t)s * cols + c]);
+        if (!(m > 0.0)) return KS_ERR_INVALID_ARG;
+        for (int c = 0; c < cols; ++c) out[(size_t)s * cols + c] = perf[(size_t)s * cols + c] / m;
+    }
+    return KS_OK;
+}
+
+extern "C" int ks_tune_prune_tree(const int64_t *features, int n_features, const double *normalised,
+                                  int rows, int cols, int max_leaves, int min_samples_leaf,
+                                  int32_t *kept_out, ks_tree_node_t *tree_out, int *tree_nodes_out) {
+    if (!features || !normalised || !kept_out || rows <= 0 || cols <= 0 || n_features <= 0 ||
+        max_leaves < 1 || min_samples_leaf < 1)
+        return KS_ERR_INVALID_ARG;
+    const Table t{features, n_features, normalised, cols, nullptr};
+    struct Node {
+        std::vector<int> rows;
+        Split split;
+        int feature = -1, left = -1, right = -1;
+        int64_t threshold = 0;
+    };
+    std::vector<Node> nodes(1);
+    nodes[0].rows.resize(rows);
+    std::iota(nodes[0].rows.begin(), nodes[0].rows.end(), 0);
+    nodes[0].split = best_split(t, nodes[0].rows, min_samples_leaf);
+    int leaves = 1;
+    while (leaves < max_leaves) {
+        int pick = -1;
+        for (int i = 0; i < (int)nodes.size(); ++i) {
+            if (nodes[i].feature != -1 || !nodes[i].split.ok) continue;
+            if (pick < 0 || better(nodes[i].split.gain, nodes[pick].split.gain)) pick = i;
+        }
+        if (pick < 0) break;
+        Node l, r;
+        partition(t, nodes[pick].rows, nodes[pick].split, l.rows, r.rows);
+        l.split = best_split(t, l.rows, min_samples_leaf);
+        r.split = best_split(t, r.rows, min_samples_leaf);
+        nodes[pick].feature = nodes[pick].split.feature;
+        nodes[pick].threshold = nodes[pick].split.threshold;
+        nodes[pick].left = (int)nodes.size();
+        nodes[pick].right = (int)nodes.size() + 1;
+        nodes.push_back(std::move(l));
+        nodes.push_back(std::move(r));
+        ++leaves;
+    }
+    std::vector<int32_t> kept;
+    for (size_t i = 0; i < nodes.size(); ++i) {
+        int value = 0;
+        if (nodes[i].feature == -1) {
+            value = argmax_mean(t, nodes[i].rows);
+            kept.push_back(value);
+        }
+        if (tree_out)
+            tree_out[i] = ks_tree_node_t{nodes[i].feature, nodes[i].left, nodes[i].right, value,
+                                         nodes[i].threshold};
+    }
+    if (tree_nodes_out) *tree_nodes_out = (int)nodes.size();
+    std::sort(kept.begin(), kept.end());
+    kept.erase(std::unique(kept.begin(), kept.end()), kept.end());
+    std::copy(kept.begin(), kept.end(), kept_out);
+    return (int)kept.size();
+}
+
+extern "C" int ks_tune_achievable(const double *normalised, int rows, int cols, const int32_t *kept,
+                                  int n_kept, double *score_out) {
+    if (!normalised || !kept || !score_out || rows <= 0 || cols <= 0 || n_kept <= 0)
+        return KS_ERR_INVALID_ARG;
+    for (int k = 0; k < n_kept; ++k) if (kept[k] < 0 || kept[k] >= cols) return KS_ERR_INVALID_ARG;
+    double logSum = 0.0;
+    for (int s = 0; s < rows; ++s) {
+        double m = 0.0;
+        for (int k = 0; k < n_kept; ++k) m = std::max(m, normalised[(size_t)s * cols + kept[k]]);
+        logSum += std::log(m);
+    }
+    *score_out = std::exp(logSum / rows);
+    return KS_OK;
+}
+
+extern "C" int ks_tune_fit_selector(const int64_t *features, int n_features, const double *perf,
+                                    int rows, int cols, const int32_t *kept, int n_kept, int max_depth,
+                                    int min_samples_leaf, const double *row_weight,
+                                    ks_tree_node_t *tree_out, int cap) {
+    if (!features || !perf || !kept || !tree_out || rows <= 0 || cols <= 0 || n_features <= 0 ||
+        n_kept <= 0 || max_depth < 0 || min_samples_leaf < 1 || cap < 1)
+        return KS_ERR_INVALID_ARG;
+    std::vector<int32_t> classId(kept, kept + n_kept);
+    std::sort(classId.begin(), classId.end());
+    classId.erase(std::unique(classId.begin(), classId.end()), classId.end());
+    for (int32_t c : classId) if (c < 0 || c >= cols) return KS_ERR_INVALID_ARG;
+    const int nc = (int)classId.size();
+    // label = fastest kept configuration of the row (lowest id on ties); targets = one-hot labels
+    std::vector<int> label(rows);
+    std::vector<double> onehot((size_t)rows * nc, 0.0);
+    for (int s = 0; s < rows; ++s) {
+        int best = 0;
+        for (int k = 1; k < nc; ++k)
+            if (perf[(size_t)s * cols + classId[k]] > perf[(size_t)s * cols + classId[best]]) best = k;
+        label[s] = best;
+        onehot[(size_t)s * nc + best] = 1.0;
+        if (row_weight && !(row_weight[s] >= 0.0)) return KS_ERR_INVALID_ARG;
+    }
+    const Table t{features, n_features, onehot.data(), nc, row_weight};
+    Grow g{t, label, classId, max_depth, min_samples_leaf, cap, {}, false};
+    std::vector<int> all(rows);
+    std::iota(all.begin(), all.end(), 0);
+    g.grow(all, 0);
+    if (g.overflow) return KS_ERR_INVALID_ARG;
+    std::copy(g.nodes.begin(), g.nodes.end(), tree_out);
+    return (int)g.nodes.size();
+}
+
+extern "C" int ks_tune_predict(const ks_tree_node_t *tree, int n_nodes, const int64_t *features,
+                               int n_features, int rows, int32_t *chosen_out) {
+    if (!tree || !features || !chosen_out || n_nodes <= 0 || rows < 0 || n_features <= 0)
+        return KS_ERR_INVALID_ARG;
+    for (int s = 0; s < rows; ++s) {
+        int i = 0, steps = 0;
+        while (tree[i].feature >= 0) {
+            if (tree[i].feature >= n_features || ++steps > n_nodes) return KS_ERR_INVALID_ARG;
+            const int next = features[(size_t)s * n_features + tree[i].feature] <= tree[i].threshold
+                                 ? tree[i].left : tree[i].right;
+            if (next <= i || next >= n_nodes) return KS_ERR_INVALID_ARG;
+            i = next;
+        }
+        chosen_out[s] = tree[i].value;
+    }
+    return KS_OK;
+}
+
+extern "C" int ks_tune_selector_score(const double *normalised, int rows, int cols,
+                                      const int32_t *chosen, double *score_out) {
+    if (!normalised || !chosen || !score_out || rows <= 0 || cols <= 0) return KS_ERR_INVALID_ARG;
+    double logSum = 0.0;
+    for (int s = 0; s < rows; ++s) {
+        if (chosen[s] < 0 || chosen[s] >= cols) return KS_ERR_INVALID_ARG;
+        logSum += std::log(normalised[(size_t)s * cols + chosen[s]]);
+    }
+    *score_out = std::exp(logSum / rows);
+    return KS_OK;
+}

@@ -1,0 +1,240 @@
+"""GPU parity: every member of the kernel family against the CPU oracle, through the C ABI."""
+import itertools
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from helpers import tolerance, c_padding_mask, operand_matrices, c_views
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = list(itertools.product((0, 1), (0, 1)))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    import gpu_util
+    return gpu_util
+
+
+def check(p, got, ref, what):
+    err = float(np.max(np.abs(got.astype(np.float64) - ref.astype(np.float64)))) if got.size else 0.0
+    tol = tolerance(p)
+    assert np.all(np.isfinite(got[~c_padding_mask(p)])), what
+    assert err <= tol, "%s: max|diff| %.3e > tol %.3e" % (what, err, tol)
+    mask = c_padding_mask(p)
+    assert np.array_equal(got[mask], p.C0[mask], equal_nan=True), what + ": wrote outside C's logical entries"
+
+
+def ids_of(gpu, dtype):
+    import paper_2003_06795_amd.binding as ks
+    return list(range(ks.num_kernels(gpu.DT[dtype])))
+
+
+def prep_workspace(gpu, p, kid):
+    import paper_2003_06795_amd.binding as ks
+    need = ks.workspace_bytes_needed(gpu.DT[p.dtype], kid, p.M, p.N, p.batch)
+    if need:
+        gpu.ensure_workspace(need)
+
+
+# ----------------------------------------------------------------------------- config 1
+
+def test_config1_four_tile_instantiations(gpu):
+    import paper_2003_06795_amd.binding as ks
+    p = wl.config1_problem()
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    wanted = set(wl.CONFIG1_TILES)
+    found = []
+    for kid in ids_of(gpu, "f32"):
+        ki = ks.kernel_info(ks.F32, kid)
+        key = (ki["bm"], ki["bn"], ki["tm"], ki["tn"], ki["bk"])
+        if ki["core_name"] == "fma" and key in wanted:
+            found.append(key)
+            check(p, dp.run(kid), ref, "config1 kernel %d" % kid)
+    assert sorted(found) == sorted(wanted)
+
+
+# ----------------------------------------------------------------------------- every kernel, every layout
+
+SHAPES_F32 = [
+    # (M, N, K, batch, pads, batch_pad)  - several tiles of the small kernels plus ragged tails
+    (200, 136, 72, 2, (0, 0, 0), (0, 0, 0)),        # multiples of 8: float4 path
+    (197, 131, 67, 2, (3, 1, 2), (5, 3, 7)),        # nothing aligned: scalar path
+    (264, 520, 40, 1, (4, 8, 4), (0, 0, 0)),        # wider than the 256 tiles, padded leading dims
+]
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+@pytest.mark.parametrize("shape", SHAPES_F32)
+def test_f32_all_kernels_within_tolerance(gpu, shape, tA, tB):
+    M, N, K, batch, pad, bpad = shape
+    p = wl.make_problem("f32", tA, tB, M, N, K, batch=batch, alpha=1.5, beta=-0.75, seed=21,
+                        key=M + 2 * tA + tB, pad=pad, batch_pad=bpad)
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    for kid in ids_of(gpu, "f32"):
+        check(p, dp.run(kid), ref, "f32 kernel %d %s tA=%d tB=%d" % (kid, shape[:3], tA, tB))
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+def test_f32_small_integers_bit_exact(gpu, tA, tB):
+    """Entries in [-8, 8] and K*64 < 2^24: every partial sum is an integer fp32 represents, so
+    any summation order gives the oracle's bits.  A wrong fragment layout cannot hide here."""
+    p = wl.make_problem("f32", tA, tB, 150, 170, 90, batch=2, alpha=1.0, beta=0.0, seed=5,
+                        key=tA * 2 + tB, dist="ints", c_fill="nan", pad=(1, 0, 3))
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    live = ~c_padding_mask(p)
+    for kid in ids_of(gpu, "f32"):
+        got = dp.run(kid)
+        assert np.array_equal(got[live], ref[live]), "kernel %d" % kid
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+def test_f32_permutation_operand_moves_rows_bit_exact(gpu, tA, tB):
+    M = K = 96
+    N = 80
+    r = np.random.default_rng(3)
+    perm = r.permutation(M)
+    P = np.zeros((M, K), dtype=np.float32)
+    P[np.arange(M), perm] = 1.0
+    X = wl.uniform_pm1(K * N, 3, 1).reshape(K, N)
+    p = wl.make_problem("f32", tA, tB, M, N, K, seed=3, c_fill="zeros")
+    p.A = np.ascontiguousarray(P.T if tA else P).ravel()
+    p.B = np.ascontiguousarray(X.T if tB else X).ravel()
+    dp = gpu.DeviceProblem(p)
+    for kid in ids_of(gpu, "f32"):
+        assert np.array_equal(dp.run(kid).reshape(M, N), X[perm, :]), "kernel %d" % kid
+
+
+SHAPES_BF16 = [
+    (264, 136, 200, 2, (0, 0, 0), (0, 0, 0)),       # multiples of 8: 16-byte path
+    (261, 131, 203, 2, (3, 1, 2), (5, 3, 7)),       # ragged: scalar path
+    (40, 520, 72, 1, (8, 8, 4), (0, 0, 0)),
+]
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+@pytest.mark.parametrize("shape", SHAPES_BF16)
+def test_bf16_all_kernels_within_tolerance(gpu, shape, tA, tB):
+    M, N, K, batch, pad, bpad = shape
+    p = wl.make_problem("bf16", tA, tB, M, N, K, batch=batch, alpha=0.5, beta=1.25, seed=22,
+                        key=M + 2 * tA + tB, pad=pad, batch_pad=bpad, dist="normal")
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    # tight diagnostic besides the stated bound: fp32 accumulation error relative to sum |a||b|
+    As, Bs, _ = operand_matrices(p)
+    mag = [np.abs(a) @ np.abs(b) for a, b in zip(As, Bs)]
+    for kid in ids_of(gpu, "bf16"):
+        prep_workspace(gpu, p, kid)
+        got = dp.run(kid)
+        check(p, got, ref, "bf16 kernel %d %s tA=%d tB=%d" % (kid, shape[:3], tA, tB))
+        for g, r_, m in zip(c_views(p, got), c_views(p, ref), mag):
+            rel = np.max(np.abs(g.astype(np.float64) - r_) / (abs(p.alpha) * m + abs(p.beta) + 1e-30))
+            assert rel < K * 2.0 ** -22, "kernel %d: accumulation error %.3e" % (kid, rel)
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+def test_bf16_small_integers_bit_exact(gpu, tA, tB):
+    p = wl.make_problem("bf16", tA, tB, 150, 170, 330, batch=2, alpha=1.0, beta=0.0, seed=6,
+                        key=tA * 2 + tB, dist="ints", c_fill="nan", pad=(1, 0, 3))
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    live = ~c_padding_mask(p)
+    for kid in ids_of(gpu, "bf16"):
+        prep_workspace(gpu, p, kid)
+        got = dp.run(kid)
+        assert np.array_equal(got[live], ref[live]), "kernel %d" % kid
+
+
+# ----------------------------------------------------------------------------- conventions and edges
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_sizes(gpu, dtype):
+    import paper_2003_06795_amd.binding as ks
+    for (M, N, K, batch) in [(0, 5, 7, 1), (5, 0, 7, 1), (5, 6, 7, 0), (5, 6, 0, 2), (1, 1, 1, 1)]:
+        for beta in (0.0, 0.5):
+            p = wl.make_problem(dtype, 0, 0, M, N, K, batch=batch, alpha=2.0, beta=beta, seed=1,
+                                c_fill="nan" if beta == 0.0 else "uniform")
+            dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+            for kid in (0, ks.num_kernels(gpu.DT[dtype]) - 1, None):
+                if kid is not None:
+                    prep_workspace(gpu, p, kid)
+                got = dp.run(kid)
+                assert np.array_equal(got, ref, equal_nan=True) or np.max(np.abs(got - ref)) <= tolerance(p)
+
+
+def test_beta_zero_ignores_nan_in_c_and_broadcast_strides(gpu):
+    p = wl.make_problem("f32", 0, 1, 70, 50, 30, batch=3, alpha=1.0, beta=0.0, seed=2, c_fill="nan",
+                        broadcast=(True, False))
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    for kid in (0, 20, 35, 53, None):
+        check(p, dp.run(kid), ref, "kernel %s" % kid)
+    p = wl.make_problem("f32", 1, 0, 70, 50, 30, batch=3, alpha=-1.0, beta=2.0, seed=2,
+                        broadcast=(False, True))
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    for kid in (6, 26, 37, None):
+        check(p, dp.run(kid), ref, "kernel %s" % kid)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_run_to_run_bitwise_determinism_and_batch_equals_loop(gpu, dtype):
+    import torch
+    import paper_2003_06795_amd.binding as ks
+    p = wl.make_problem(dtype, 0, 0, 130, 140, 260, batch=3, alpha=1.0, beta=0.5, seed=9,
+                        dist="normal" if dtype == "bf16" else "uniform")
+    dp = gpu.DeviceProblem(p)
+    for kid in ids_of(gpu, dtype):
+        prep_workspace(gpu, p, kid)
+        a, b = dp.run(kid), dp.run(kid)
+        assert np.array_equal(a, b), "kernel %d is not deterministic" % kid
+        # the same three items as three single calls
+        C = dp.C0.clone()
+        fn = ks.gemm_f32_with_kernel if dtype == "f32" else ks.gemm_bf16_with_kernel
+        esz = 4 if dtype == "f32" else 2
+        for t in range(p.batch):
+            fn(kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha,
+               dp.A.data_ptr() + t * p.strideA * esz, p.lda, dp.B.data_ptr() + t * p.strideB * esz,
+               p.ldb, p.beta, C.data_ptr() + t * p.strideC * 4, p.ldc, 1, 0, 0, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), a), "kernel %d: batched != looped" % kid
+
+
+def test_argument_errors_launch_nothing(gpu):
+    import torch
+    import paper_2003_06795_amd.binding as ks
+    A = torch.ones(64, device="cuda:0")
+    C = torch.full((64,), 7.0, device="cuda:0")
+    bad = [
+        dict(transA=2), dict(M=-1), dict(lda=3), dict(ldb=3), dict(ldc=3), dict(A=0), dict(C=0),
+        dict(batch=2, strideC=8), dict(kernel_id=64), dict(kernel_id=-1),
+    ]
+    base = dict(kernel_id=0, transA=0, transB=0, M=4, N=4, K=4, alpha=1.0, A=A, lda=4, B=A, ldb=4,
+                beta=0.0, C=C, ldc=4, batch=1, strideA=0, strideB=0, strideC=0)
+    for change in bad:
+        kw = dict(base)
+        kw.update(change)
+        with pytest.raises(ks.KsError) as e:
+            ks.gemm_f32_with_kernel(**kw)
+        assert e.value.status == ks.ERR_INVALID_ARG, change
+    with pytest.raises(ks.KsError) as e:
+        ks.gemm_f32_with_kernel(**dict(base, M=2 ** 31))
+    assert e.value.status == ks.ERR_UNSUPPORTED
+    ks.set_workspace(None)
+    with pytest.raises(ks.KsError) as e:
+        ks.gemm_bf16_with_kernel(17, 0, 0, 4, 4, 4, 1.0, A, 4, A, 4, 0.0, C, 4)
+    assert e.value.status == ks.ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(C == 7.0)
+    import gpu_util
+    gpu_util.ensure_workspace.__defaults__[0].clear()
+
+
+def test_selected_call_equals_forced_call_bitwise(gpu):
+    import paper_2003_06795_amd.binding as ks
+    for dtype, shape in (("f32", (300, 200, 100)), ("bf16", (300, 200, 128))):
+        p = wl.make_problem(dtype, 0, 1, *shape, batch=2, alpha=1.0, beta=0.25, seed=4)
+        dp = gpu.DeviceProblem(p)
+        kid = ks.select(gpu.DT[dtype], p.M, p.N, p.K, p.batch, p.transA, p.transB)
+        prep_workspace(gpu, p, kid)
+        assert np.array_equal(dp.run(None), dp.run(kid))

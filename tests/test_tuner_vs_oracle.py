@@ -1,0 +1,118 @@
+"""The library's C++ tuner (normalise, prune, score, fit selector, predict) against the numpy
+oracle of the same pipeline, on seeded synthetic timing tables.  CPU only."""
+import numpy as np
+import pytest
+
+import paper_2003_06795_amd.binding as ks
+from oracle import selection as sel
+
+
+def table(rows, cols, seed, structured=True):
+    r = np.random.default_rng(seed)
+    M, N, K = (np.exp(r.uniform(np.log(16), np.log(4096), rows)).astype(np.int64) // 8 * 8 + 8 for _ in range(3))
+    tA, tB = r.integers(0, 2, rows), r.integers(0, 2, rows)
+    X = np.stack([ks.features(int(m), int(n), int(k), 1, int(a), int(b))
+                  for m, n, k, a, b in zip(M, N, K, tA, tB)])
+    P = (r.random((rows, cols)) * 0.3 + 0.1)
+    if structured:
+        # a few configurations that are each good in one region of the size space
+        size = np.log2(X[:, 6].astype(np.float64))
+        for c in range(min(cols, 6)):
+            lo = 8 + 2.5 * c
+            P[:, c] += np.where((size >= lo) & (size < lo + 2.5), 1.0, 0.0) * (1 + 0.3 * tA * (c % 2))
+    return X, P * 1e12
+
+
+def same_tree(ours, ref, leaf_key):
+    """Structural equality: same splits in the same positions, same leaf payloads."""
+    def walk(i, j):
+        a, b = ours[i], ref[j]
+        if b["feature"] == -1:
+            assert a["feature"] < 0
+            assert int(a["value"]) == leaf_key(b)
+            return
+        assert (int(a["feature"]), int(a["threshold"])) == (b["feature"], b["threshold"])
+        walk(int(a["left"]), b["left"])
+        walk(int(a["right"]), b["right"])
+    walk(0, 0)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("nfeat", [ks.NUM_RAW_FEATURES, ks.NUM_FEATURES])
+def test_whole_pipeline_matches_oracle(seed, nfeat):
+    X, P = table(220, 24, seed)
+    X = X[:, :nfeat]
+    Xtr, Ptr, Xte, Pte = X[:150], P[:150], X[150:], P[150:]
+    Ph = ks.tune_normalise(Ptr)
+    assert np.array_equal(Ph, sel.normalise(Ptr))
+    Ph_te = ks.tune_normalise(Pte)
+    for n_kept in (1, 4, 6, 8, 15):
+        kept, reg = ks.tune_prune_tree(Xtr, Ph, n_kept)
+        ref_reg = sel.fit_regression_tree(Xtr, sel.normalise(Ptr), n_kept)
+        assert kept.tolist() == sel.kept_set(ref_reg)
+        assert len(reg) == len(ref_reg)
+        same_tree(reg, ref_reg, lambda nd: int(np.argmax(nd["value"])))
+        assert ks.tune_achievable(Ph_te, kept) == pytest.approx(sel.achievable(sel.normalise(Pte), kept), rel=1e-13)
+        for depth in (3, 12):
+            tree = ks.tune_fit_selector(Xtr, Ptr, kept, max_depth=depth)
+            ref = sel.fit_classification_tree(Xtr, sel.labels_within(Ptr, kept), max_depth=depth)
+            assert len(tree) == len(ref)
+            same_tree(tree, ref, lambda nd: nd["label"])
+            chosen = ks.tune_predict(tree, Xte)
+            assert np.array_equal(chosen, sel.predict_labels(ref, Xte))
+            s = ks.tune_selector_score(Ph_te, chosen)
+            assert s == pytest.approx(sel.selector_score(sel.normalise(Pte), chosen), rel=1e-13)
+            assert s <= ks.tune_achievable(Ph_te, kept) + 1e-15
+
+
+def test_unstructured_table_and_min_samples_leaf():
+    X, P = table(120, 10, 5, structured=False)
+    Ph = ks.tune_normalise(P)
+    for msl in (1, 5):
+        kept, reg = ks.tune_prune_tree(X, Ph, 6, min_samples_leaf=msl)
+        ref = sel.fit_regression_tree(X, sel.normalise(P), 6, min_samples_leaf=msl)
+        assert kept.tolist() == sel.kept_set(ref)
+        same_tree(reg, ref, lambda nd: int(np.argmax(nd["value"])))
+        tree = ks.tune_fit_selector(X, P, kept, max_depth=6, min_samples_leaf=msl)
+        ref = sel.fit_classification_tree(X, sel.labels_within(P, kept), max_depth=6, min_samples_leaf=msl)
+        same_tree(tree, ref, lambda nd: nd["label"])
+
+
+def test_training_is_reproducible_byte_for_byte_and_deploys():
+    X, P = table(200, 16, 9)
+    Ph = ks.tune_normalise(P)
+    a = ks.tune_fit_selector(X, P, ks.tune_prune_tree(X, Ph, 8)[0])
+    b = ks.tune_fit_selector(X.copy(), P.copy(), ks.tune_prune_tree(X.copy(), Ph.copy(), 8)[0])
+    assert a.tobytes() == b.tobytes()
+    try:
+        ks.set_selector(ks.F32, a)
+        r = np.random.default_rng(2)
+        shapes = [(int(np.exp(r.uniform(0, 13))), int(np.exp(r.uniform(0, 13))), int(np.exp(r.uniform(0, 13))),
+                   1, int(r.integers(0, 2)), int(r.integers(0, 2))) for _ in range(20000)]
+        F = np.stack([ks.features(*s) for s in shapes[:2000]])
+        deployed = np.array([ks.select(ks.F32, *s) for s in shapes[:2000]])
+        assert np.array_equal(deployed, ks.tune_predict(a, F))
+    finally:
+        ks.set_selector(ks.F32, None)
+
+
+def test_row_weights_steer_the_classifier():
+    X, P = table(100, 6, 3)
+    kept = np.array([0, 1, 2], dtype=np.int32)
+    y = sel.labels_within(P, kept)
+    w = np.where(y == 2, 100.0, 1.0)
+    plain = ks.tune_fit_selector(X, P, kept, max_depth=1)
+    weighted = ks.tune_fit_selector(X, P, kept, max_depth=1, row_weight=w)
+    leaves = lambda t: sorted(int(n["value"]) for n in t if n["feature"] < 0)
+    assert 2 in leaves(weighted)
+    assert np.array_equal(ks.tune_fit_selector(X, P, kept, max_depth=1, row_weight=np.ones(100)), plain)
+
+
+def test_bad_arguments():
+    X, P = table(20, 4, 0)
+    with pytest.raises(ks.KsError):
+        ks.tune_achievable(ks.tune_normalise(P), [9])
+    with pytest.raises(ks.KsError):
+        ks.tune_selector_score(ks.tune_normalise(P), np.full(20, 4))
+    with pytest.raises(ks.KsError):
+        ks.tune_normalise(np.zeros((3, 3)))
