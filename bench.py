@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg5]
+
+A step is one pass of the deployed library over the workload: for every (shape, layout) row,
+ks_select picks a kernel and ks_gemm_* runs it (inputs resident in HBM).  The default workload is
+the fp32 tuning set (200 log-uniform shapes x 4 layouts = 800 GEMMs); `value` is the geometric
+mean over rows of TFLOP/s, each row's time being the median over the K timed steps of the HIP
+event interval around its launch.  One JSON line is printed with the roofline of the dominant
+kernel and the CPU oracle timed on a bounded sample of the same rows.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"f32": 157.3, "bf16": 2516.6}      # dense matrix-core TFLOP/s of MI355X
+HBM_PEAK_GBS = 8000.0
+
+
+def kernel_symbol(ks, dt, kid, tA, tB, vec=True):
+    ki = ks.kernel_info(dt, kid)
+    akc, bkc = int(not tA), int(bool(tB))
+    b = lambda v: "true" if v else "false"
+    if dt == ks.F32:
+        p1, p2 = (ki["tm"], ki["tn"]) if ki["core_name"] == "fma" else (ki["wm"], ki["wn"])
+        return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s>" % (
+            ki["core"], ki["bm"], ki["bn"], ki["bk"], p1, p2, b(akc), b(bkc), b(vec))
+    f = 16 if ki["core_name"] == "mfma16" else 32
+    return "gemm_bf16_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s>" % (
+        f, ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], b(akc), b(bkc), b(vec))
+
+
+def build_rows(workload):
+    import workloads as wl
+    rows = []
+    if workload == "cfg2":
+        for (s, tA, tB, M, N, K, b) in wl.config2_rows():
+            rows.append(dict(dtype="f32", shape=s, tA=tA, tB=tB, M=M, N=N, K=K, batch=b, alpha=1.0, beta=0.0))
+    elif workload == "cfg5":
+        for s, (M, N, K) in enumerate(wl.config5_shapes()):
+            for (tA, tB) in wl.CONFIG5_LAYOUTS:
+                rows.append(dict(dtype="bf16", shape=s, tA=tA, tB=tB, M=M, N=N, K=K, batch=1, alpha=1.0, beta=0.0))
+    else:
+        raise SystemExit("unknown workload %r" % workload)
+    return rows
+
+
+def allocate(rows, torch):
+    """One (A, B, C) set per distinct shape; the layouts of a shape reinterpret the same buffers."""
+    g = torch.Generator(device="cuda")
+    bufs = {}
+    for r in rows:
+        key = (r["dtype"], r["shape"])
+        if key in bufs:
+            continue
+        g.manual_seed(1000 + r["shape"])
+        M, N, K, b = r["M"], r["N"], r["K"], r["batch"]
+        if r["dtype"] == "f32":
+            A = torch.rand(M * K * b, generator=g, device="cuda") * 2 - 1
+            B = torch.rand(K * N * b, generator=g, device="cuda") * 2 - 1
+        else:
+            s = 1.0 / np.sqrt(K)
+            A = (torch.randn(M * K * b, generator=g, device="cuda") * s).to(torch.bfloat16)
+            B = (torch.randn(K * N * b, generator=g, device="cuda") * s).to(torch.bfloat16)
+        C = torch.zeros(M * N * b, device="cuda")
+        bufs[key] = (A, B, C)
+    return bufs
+
+
+def run_pass(ks, rows, bufs, torch, events=None, reps=None):
+    """One pass: every row's GEMM, launched reps[i] times back to back between its event pair."""
+    for i, r in enumerate(rows):
+        A, B, C = bufs[(r["dtype"], r["shape"])]
+        M, N, K, b = r["M"], r["N"], r["K"], r["batch"]
+        fn = ks.gemm_f32 if r["dtype"] == "f32" else ks.gemm_bf16
+        if events is not None:
+            events[i][0].record()
+        for _ in range(1 if reps is None else reps[i]):
+            fn(r["tA"], r["tB"], M, N, K, r["alpha"], A, M if r["tA"] else K, B, K if r["tB"] else N,
+               r["beta"], C, N, b, M * K if b > 1 else 0, K * N if b > 1 else 0, M * N if b > 1 else 0)
+        if events is not None:
+            events[i][1].record()
+
+
+def cpu_baseline(rows, budget_s=15.0):
+    """The CPU oracle, as it stands, on a seeded sample of the same rows (small ones first so the
+    sample is bounded); reports the geometric mean of its TFLOP/s over the sampled rows."""
+    import workloads as wl
+    from oracle import gemm as og
+    order = np.random.default_rng(0).permutation(len(rows))
+    picked, rates, spent = [], [], 0.0
+    for i in order:
+        r = rows[int(i)]
+        macs = r["M"] * r["N"] * r["K"] * r["batch"]
+        if macs > 2 ** 31 or spent > budget_s:
+            continue
+        p = wl.make_problem(r["dtype"], r["tA"], r["tB"], r["M"], r["N"], r["K"], batch=r["batch"],
+                            alpha=r["alpha"], beta=r["beta"], seed=1, key=int(i),
+                            dist="normal" if r["dtype"] == "bf16" else "uniform")
+        C = p.C0.copy()
+        t0 = time.perf_counter()
+        og.gemm(p.dtype, p.transA, p.transB, p.M, p.N, p.K, p.alpha, p.A, p.lda, p.B, p.ldb, p.beta, C,
+                p.ldc, p.batch, p.strideA, p.strideB, p.strideC)
+        dt = time.perf_counter() - t0
+        spent += dt
+        picked.append(int(i))
+        rates.append(2.0 * macs / dt / 1e12)
+        if len(picked) >= 40:
+            break
+    return dict(value=float(np.exp(np.mean(np.log(rates)))), unit="TFLOP/s (geomean over sampled rows)",
+                cores=og.num_threads(), kind="oracle",
+                sample="%d seeded rows of the workload with M*N*K <= 2^31, full fp64 triple loop, %.1f s of CPU work"
+                       % (len(picked), spent))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-extra", action="store_true", help="skip the bf16 large-shape report")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md); "
+                         "run with --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs an MI355X (no CPU fallback exists)")
+    import paper_2003_06795_amd.binding as ks
+
+    rows = build_rows(a.workload)
+    dtype = rows[0]["dtype"]
+    dt = ks.F32 if dtype == "f32" else ks.BF16
+    bufs = allocate(rows, torch)
+    need = max(ks.workspace_bytes_needed(dt, ks.select(dt, r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"]),
+                                         r["M"], r["N"], r["batch"]) for r in rows)
+    ws = None
+    if need:
+        ws = torch.empty(need // 4 + 1, dtype=torch.float32, device="cuda")
+        ks.set_workspace(ws)
+
+    # Like the tuner, a row's sample is a short run of back-to-back launches so that the event
+    # interval measures kernel time rather than the gap between two dependent packets.  The
+    # repetition count is a fixed function of the row's flops (about 3e8 flops per sample, at
+    # most 16 launches), so warm-up and timed passes launch exactly the same kernels.
+    reps = [int(min(16, max(1, np.ceil(3e8 / (2.0 * r["M"] * r["N"] * r["K"] * r["batch"]))))) for r in rows]
+    for _ in range(a.warmup):
+        run_pass(ks, rows, bufs, torch, None, reps)
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in rows] for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(a.steps):
+        run_pass(ks, rows, bufs, torch, events[s], reps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    # per-launch milliseconds, steps x rows
+    ms = np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in events]) / np.array(reps)[None, :]
+    med = np.median(ms, axis=0)
+    flops = np.array([2.0 * r["M"] * r["N"] * r["K"] * r["batch"] for r in rows])
+    tflops = flops / (med * 1e-3) / 1e12
+    value = float(np.exp(np.mean(np.log(tflops))))
+
+    # dominant kernel symbol: the instantiation with the most device time in a step
+    chosen = [ks.select(dt, r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"]) for r in rows]
+    sym = [kernel_symbol(ks, dt, k, r["tA"], r["tB"]) for k, r in zip(chosen, rows)]
+    by = {}
+    for i, s in enumerate(sym):
+        d = by.setdefault(s, dict(time=0.0, flops=0.0, bytes=0.0, launches=0))
+        n = a.steps * reps[i]
+        d["time"] += float(ms[:, i].sum()) * 1e-3 * reps[i]
+        d["flops"] += float(flops[i]) * n
+        r = rows[i]
+        esz = 4 if dtype == "f32" else 2
+        d["bytes"] += n * r["batch"] * ((r["M"] * r["K"] + r["K"] * r["N"]) * esz + r["M"] * r["N"] * 4)
+        d["launches"] += n
+    dom = max(by, key=lambda s: by[s]["time"])
+    d = by[dom]
+    achieved = d["flops"] / d["time"] / 1e12
+    roofline = dict(bound="mfma", kernel=dom, achieved=achieved, peak=PEAK[dtype], unit="TFLOP/s",
+                    frac=achieved / PEAK[dtype], traffic=None, launches_per_step=d["launches"] // a.steps,
+                    avg_launch_us=d["time"] / d["launches"] * 1e6,
+                    share_of_step_time=d["time"] / float((ms * np.array(reps)[None, :]).sum() * 1e-3),
+                    algorithmic_gbs=d["bytes"] / d["time"] / 1e9)
+
+    out = {
+        "metric": "GEMM TFLOP/s geomean over shape set; selected/exhaustive-best perf ratio",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": wall / a.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": ("fp32 tuning set: 200 log-uniform shapes in [16,4096]^3 (seed 1) x 4 layouts, "
+                                "selected kernel per row" if a.workload == "cfg2" else
+                                "bf16 large/skinny set: 7 shapes x {NN,NT}, selected kernel per row"),
+                   "rows": len(rows), "kernels_used": len(set(chosen)),
+                   "launches_per_step": int(sum(reps)),
+                   "timing": "per row: median over steps of (HIP-event interval around reps back-to-back launches) / reps"},
+        "device_ms_per_step": float((ms * np.array(reps)[None, :]).sum() / a.steps),
+        "best_row_tflops": float(tflops.max()),
+        "roofline": roofline,
+    }
+    # selector quality measured offline on the stored exhaustive sweep (held-out shapes)
+    rep = os.path.join(ROOT, "paper_2003_06795_amd", "tune", "data", "tree_%s.json" % dtype)
+    if os.path.exists(rep):
+        R = json.load(open(rep))
+        dep = [s for s in R["sweep"] if s["n_kept"] == R["deployed"]["n_kept"]][0]
+        out["selector"] = dict(source="stored exhaustive sweep, held-out 30% of shapes", n_kept=dep["n_kept"],
+                               kept=dep["kept"], selected_over_best_geomean=dep["test"]["selector"],
+                               achievable_geomean=dep["test"]["achievable"])
+    if not a.no_extra and a.workload == "cfg2":
+        out["bf16_large"] = bf16_report(ks, torch)
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(rows)
+    print(json.dumps(out))
+
+
+def bf16_report(ks, torch):
+    """Selected bf16 kernels on the large/skinny set: TFLOP/s and fraction of the bf16 matrix peak."""
+    rows = build_rows("cfg5")
+    bufs = allocate(rows, torch)
+    ws = torch.empty(64 * 256 * 256 + 4 * 8192 * 256 + 1024, dtype=torch.float32, device="cuda")
+    ks.set_workspace(ws)
+    cells = []
+    for r in rows:
+        A, B, C = bufs[(r["dtype"], r["shape"])]
+        M, N, K = r["M"], r["N"], r["K"]
+        kid = ks.select(ks.BF16, M, N, K, 1, r["tA"], r["tB"])
+        if ks.workspace_bytes_needed(ks.BF16, kid, M, N, 1) > ws.numel() * 4:
+            continue
+        t = ks.time_gemm(ks.BF16, kid, r["tA"], r["tB"], M, N, K, 1.0, A, M if r["tA"] else K, B,
+                         K if r["tB"] else N, 0.0, C, N, warmup=2, iters=5, reps=1)
+        tf = 2.0 * M * N * K / (float(np.median(t)) * 1e-3) / 1e12
+        gbs = ((M * K + K * N) * 2 + M * N * 4) / (float(np.median(t)) * 1e-3) / 1e9
+        cells.append(dict(M=M, N=N, K=K, layout="N" + "NT"[r["tB"]], kernel=kid, tflops=tf,
+                          frac_of_bf16_peak=tf / PEAK["bf16"], algorithmic_gbs=gbs))
+    ks.set_workspace(None)
+    big = [c["tflops"] for c in cells if min(c["M"], c["N"]) >= 2048]
+    return dict(cells=cells, geomean_tflops=float(np.exp(np.mean(np.log([c["tflops"] for c in cells])))),
+                best_frac_of_peak=max(big) / PEAK["bf16"] if big else None)
+
+
+if __name__ == "__main__":
+    main()

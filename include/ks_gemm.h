@@ -146,6 +146,12 @@ int ks_set_selector(int dtype, const ks_tree_node_t *nodes, int n);
  * too small. */
 int ks_get_selector(int dtype, ks_tree_node_t *nodes, int cap);
 
+/* The bf16 instantiations have two code paths with the same tiles: a generic one (any alignment,
+ * any K) and a direct-to-LDS one used when operands are 16-byte aligned, leading dimensions and
+ * contiguous extents are multiples of 8 and K is a multiple of the K-step.  enabled == 0 forces
+ * the generic path (for testing it at aligned shapes); nonzero restores the default. */
+int ks_set_fast_path(int enabled);
+
 /* ---------------------------------------------------------------- workspace
  * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no
  * atomics) need split_k * batch * M * N floats of scratch.  The caller registers one device

@@ -34,7 +34,7 @@ def _deps():
 def _jobs():
     jobs = []
     for n in range(SHARDS):
-        for kind in ("f32", "bf16"):
+        for kind in ("f32", "bf16", "bf16_dma"):
             src = os.path.join(CSRC, "instances_%s.hip" % kind)
             jobs.append((src, os.path.join(OBJ, "inst_%s_%02d.o" % (kind, n)),
                          [HIPCC] + HIP_FLAGS + ["-DKS_SHARD=%d" % n, "-c", src]))

@@ -11,7 +11,8 @@ namespace ks {
 
 #define KS_DECL(n)                              \
     void register_f32_shard_##n(LaunchFn *);    \
-    void register_bf16_shard_##n(LaunchFn *);
+    void register_bf16_shard_##n(LaunchFn *);   \
+    void register_bf16_dma_shard_##n(LaunchFn *);
 KS_DECL(0) KS_DECL(1) KS_DECL(2) KS_DECL(3) KS_DECL(4) KS_DECL(5) KS_DECL(6) KS_DECL(7)
 KS_DECL(8) KS_DECL(9) KS_DECL(10) KS_DECL(11) KS_DECL(12) KS_DECL(13) KS_DECL(14) KS_DECL(15)
 #undef KS_DECL
@@ -43,6 +44,7 @@ const InstanceDesc kBf16[kNumBf16] = {
 
 LaunchFn g_f32[kNumF32];
 LaunchFn g_bf16[kNumBf16];
+LaunchFn g_bf16_dma[kNumBf16];
 std::once_flag g_once;
 
 void init_tables() {
@@ -58,8 +60,17 @@ void init_tables() {
     register_bf16_shard_9(g_bf16); register_bf16_shard_10(g_bf16); register_bf16_shard_11(g_bf16);
     register_bf16_shard_12(g_bf16); register_bf16_shard_13(g_bf16); register_bf16_shard_14(g_bf16);
     register_bf16_shard_15(g_bf16);
+    register_bf16_dma_shard_0(g_bf16_dma); register_bf16_dma_shard_1(g_bf16_dma);
+    register_bf16_dma_shard_2(g_bf16_dma); register_bf16_dma_shard_3(g_bf16_dma);
+    register_bf16_dma_shard_4(g_bf16_dma); register_bf16_dma_shard_5(g_bf16_dma);
+    register_bf16_dma_shard_6(g_bf16_dma); register_bf16_dma_shard_7(g_bf16_dma);
+    register_bf16_dma_shard_8(g_bf16_dma); register_bf16_dma_shard_9(g_bf16_dma);
+    register_bf16_dma_shard_10(g_bf16_dma); register_bf16_dma_shard_11(g_bf16_dma);
+    register_bf16_dma_shard_12(g_bf16_dma); register_bf16_dma_shard_13(g_bf16_dma);
+    register_bf16_dma_shard_14(g_bf16_dma); register_bf16_dma_shard_15(g_bf16_dma);
 }
 
+int g_forceGeneric = 0;
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
@@ -168,7 +179,14 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
                      (batch == 1 || (strideA % w == 0 && strideB % w == 0));
     const int variant = (akc ? 4 : 0) + (bkc ? 2 : 0) + (vec ? 1 : 0);
 
-    (dtype == KS_F32 ? g_f32[id] : g_bf16[id])(p, (int)grid64, variant, stream);
+    // bf16 fast path: operand tiles go global -> LDS directly.  Needs 16-byte accesses, whole
+    // K-steps, and tile-relative byte offsets that fit 32 bits.
+    const bool dma = dtype == KS_BF16 && vec && g_forceGeneric == 0 && K % d->bk == 0 &&
+                     lda <= (1LL << 22) && ldb <= (1LL << 22);
+    if (dma)
+        g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0), stream);
+    else
+        (dtype == KS_F32 ? g_f32[id] : g_bf16[id])(p, (int)grid64, variant, stream);
     if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
 
     if (p.splitK > 1) {
@@ -209,6 +227,11 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     out->threads = d->threads;
     out->split_k = d->splitK;
     out->lds_bytes = d->ldsBytes;
+    return KS_OK;
+}
+
+extern "C" int ks_set_fast_path(int enabled) {
+    g_forceGeneric = enabled ? 0 : 1;
     return KS_OK;
 }
 

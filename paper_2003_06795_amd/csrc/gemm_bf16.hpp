@@ -201,25 +201,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_kernel(c
     }
     (void)LGRP;
 
-    if constexpr (F == 16) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    store_entry(p, tc, Cb, row0 + subM + i * 16 + 4 * (lane >> 4) + e,
-                                col0 + subN + j * 16 + (lane & 15), acc16[i][j][e]);
-    } else {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    store_entry(p, tc, Cb, row0 + subM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3),
-                                col0 + subN + j * 32 + (lane & 31), acc32[i][j][e]);
-    }
+    if constexpr (F == 16)
+        write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
+    else
+        write_tile_mfma32<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
 }
 
 }  // namespace ks

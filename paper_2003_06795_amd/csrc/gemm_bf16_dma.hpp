@@ -1,0 +1,226 @@
+// bf16 fast path of the tiled GEMM family (paper Section II): the same instantiations as
+// gemm_bf16.hpp (work-group tile BM x BN, K-step BK, wave tile WM x WN, fragment F), but the
+// operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, 16 bytes per
+// lane, no staging registers) one K-step ahead of the MFMAs.
+//
+// Preconditions (checked by the host, which otherwise launches the generic kernel):
+//   16-byte aligned operands, leading dimensions and contiguous extents multiples of 8,
+//   K a multiple of BK, tile-relative byte offsets below 2^31.
+// Rows beyond M / N are clamped to the last valid row (the results they feed are never stored).
+//
+// LDS layouts
+//   K-contiguous operand (A not transposed, B transposed):  tile[row][BK]; the 16-byte chunk c of
+//     row r sits at chunk position c ^ swz(r) (Bf16Lds), read with ds_read_b128.
+//   row-contiguous operand (A transposed, B not transposed): tile[k][ROWS] exactly as in memory;
+//     32-byte units are XOR-swizzled by k.  The MFMA operand (8 consecutive k of one row per
+//     lane) is produced by the transposing LDS read ds_read_b64_tr_b16: inside each group of 16
+//     lanes, lane s supplies the address of 4 consecutive rows at k = kb + s/4, and lane l
+//     receives the 4 values k = kb .. kb+3 of row l.
+//
+// A direct-to-LDS load writes LDS_base(wave-uniform) + lane * 16, i.e. one instruction fills 1 KiB
+// of the tile; the swizzle is applied by choosing which global chunk each lane fetches.
+#pragma once
+#include "gemm_bf16.hpp"
+
+namespace ks {
+
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+template <int ROWS>
+struct Bf16LdsT {
+    static constexpr int CPR = ROWS / 8;                    // 16-byte chunks per k row
+    static constexpr int UPR = ROWS / 16;                   // 32-byte units per k row
+    // XOR applied to the 32-byte unit index of k row `k`
+    __device__ __forceinline__ static int swz(int k) {
+        if constexpr (UPR >= 8) return k & 7;
+        else if constexpr (UPR == 4) return (k >> 1) & 3;
+        else if constexpr (UPR == 2) return (k >> 2) & 1;
+        else return 0;
+    }
+    // byte offset of element (k, row) for row a multiple of 4
+    __device__ __forceinline__ static int byte_of(int k, int row) {
+        return k * (ROWS * 2) + ((((row >> 4) ^ swz(k)) << 5) | ((row & 15) << 1));
+    }
+};
+
+// Per-lane source offsets of the direct-to-LDS loads of one operand tile.
+template <int ROWS, int BK, int NW, bool KC>
+struct DmaPlan {
+    static constexpr int TOTAL = ROWS * BK / 512;            // 1 KiB instructions per tile
+    static constexpr int PER_WAVE = (TOTAL + NW - 1) / NW;
+    unsigned off[PER_WAVE];                                  // byte offset from the tile origin
+
+    // origin: element (row0, k = 0) of the operand; limit = number of valid rows from row 0
+    __device__ __forceinline__ void init(int wave, int lane, long long ld, int row0, int limit) {
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int L = (wave + j * NW) * 64 + lane;       // chunk slot in the LDS tile
+            if constexpr (KC) {
+                constexpr int CPR = BK / 8;
+                const int r = L / CPR, pos = L % CPR;
+                const int c = pos ^ ((r / (16 / CPR)) & (CPR - 1));
+                const int row = min(row0 + r, limit - 1) - row0;
+                off[j] = (unsigned)(((long long)row * ld + c * 8) * 2);
+            } else {
+                constexpr int CPR = ROWS / 8;
+                const int k = L / CPR, pos = L % CPR;
+                const int c = pos ^ (2 * Bf16LdsT<ROWS>::swz(k));
+                const int row = min(row0 + c * 8, limit - 8) - row0;
+                off[j] = (unsigned)(((long long)k * ld + row) * 2);
+            }
+        }
+    }
+
+    // tile: global address of the tile origin at this K-step (wave-uniform); lds: stage base
+    __device__ __forceinline__ void issue(const char *tile, char *lds, int wave) const {
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int i = wave + j * NW;
+            if (TOTAL % NW == 0 || i < TOTAL)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(tile + off[j]),
+                    (lds_void_ptr)(lds + i * 1024), 16, 0, 0);
+        }
+    }
+};
+
+template <int F, int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC>
+__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kernel(const GemmParams p) {
+    constexpr int NW = (BM / WM) * (BN / WN);
+    constexpr int FM = WM / F, FN = WN / F;
+    constexpr int KSTEP = F == 32 ? 16 : 32;
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    using LK = Bf16Lds<BK>;
+    __shared__ __attribute__((aligned(1024))) char As0[A_BYTES];
+    __shared__ __attribute__((aligned(1024))) char As1[A_BYTES];
+    __shared__ __attribute__((aligned(1024))) char Bs0[B_BYTES];
+    __shared__ __attribute__((aligned(1024))) char Bs1[B_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const TileCoord tc = tile_of_block(p);
+    const int row0 = tc.tm * BM, col0 = tc.tn * BN;
+    const int kBegin = tc.split * p.kChunk;
+    const int kEnd = min(p.K, kBegin + p.kChunk);
+    const int nk = (kEnd - kBegin) / BK;
+    const uint16_t *Ab = static_cast<const uint16_t *>(p.A) + (long long)tc.batch * p.strideA;
+    const uint16_t *Bb = static_cast<const uint16_t *>(p.B) + (long long)tc.batch * p.strideB;
+    float *Cb = p.C + (long long)tc.batch * p.strideC;
+    // tile origins at k = kBegin and their advance per K-step, in bytes
+    const char *aTile = reinterpret_cast<const char *>(AKC ? Ab + (long long)row0 * p.lda + kBegin
+                                                            : Ab + (long long)kBegin * p.lda + row0);
+    const char *bTile = reinterpret_cast<const char *>(BKC ? Bb + (long long)col0 * p.ldb + kBegin
+                                                            : Bb + (long long)kBegin * p.ldb + col0);
+    const long long aStep = AKC ? BK * 2LL : BK * 2LL * p.lda;
+    const long long bStep = BKC ? BK * 2LL : BK * 2LL * p.ldb;
+
+    DmaPlan<BM, BK, NW, AKC> pa;
+    DmaPlan<BN, BK, NW, BKC> pb;
+    pa.init(wave, lane, p.lda, row0, p.M);
+    pb.init(wave, lane, p.ldb, col0, p.N);
+
+    const int subM = (wave / (BN / WN)) * WM, subN = (wave % (BN / WN)) * WN;
+    const int lrow = lane % F, lgrp = lane / F;
+    // transposing read: lane s of a 16-lane group addresses rows 4*(s%4).. of k row s/4 (+ group base)
+    const int trRow = 4 * (lane & 3) + (F == 32 ? 16 * ((lane >> 4) & 1) : 0);
+    const int trK = (lane & 15) >> 2;
+
+    floatx4 acc16[F == 16 ? FM : 1][F == 16 ? FN : 1];
+    floatx16 acc32[F == 32 ? FM : 1][F == 32 ? FN : 1];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            if constexpr (F == 16) acc16[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+            else
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+        }
+
+    auto compute = [&](const char *as, const char *bs) {
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += KSTEP) {
+            bf16x8 a[FM], b[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                if constexpr (AKC) {
+                    a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
+                        as + 16 * LK::chunk(subM + i * F + lrow, kk / 8 + lgrp)));
+                } else {
+                    using LT = Bf16LdsT<BM>;
+                    const int kb = kk + 8 * lgrp + trK;
+                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb, subM + i * F + trRow)));
+                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb + 4, subM + i * F + trRow)));
+                    typedef short shortx8 __attribute__((ext_vector_type(8)));
+                    const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    a[i] = __builtin_bit_cast(bf16x8, v);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                if constexpr (BKC) {
+                    b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
+                        bs + 16 * LK::chunk(subN + j * F + lrow, kk / 8 + lgrp)));
+                } else {
+                    using LT = Bf16LdsT<BN>;
+                    const int kb = kk + 8 * lgrp + trK;
+                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb, subN + j * F + trRow)));
+                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb + 4, subN + j * F + trRow)));
+                    typedef short shortx8 __attribute__((ext_vector_type(8)));
+                    const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    b[j] = __builtin_bit_cast(bf16x8, v);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    if constexpr (F == 16)
+                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc16[i][j], 0, 0, 0);
+                    else
+                        acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc32[i][j], 0, 0, 0);
+                }
+        }
+    };
+
+    // every wave waits for its own direct-to-LDS loads before the barrier publishes the stage
+    auto publish = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), other counters untouched
+        __syncthreads();
+    };
+
+    if (nk > 0) {
+        pa.issue(aTile, As0, wave);
+        pb.issue(bTile, Bs0, wave);
+    }
+    publish();
+    // two K-steps per trip so that the stage being filled and the stage being read are different
+    // __shared__ objects
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        pa.issue(aTile + (kt + 1) * aStep, As1, wave);
+        pb.issue(bTile + (kt + 1) * bStep, Bs1, wave);
+        __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the MFMAs they overlap
+        compute(As0, Bs0);
+        publish();
+        if (kt + 2 < nk) {
+            pa.issue(aTile + (kt + 2) * aStep, As0, wave);
+            pb.issue(bTile + (kt + 2) * bStep, Bs0, wave);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        compute(As1, Bs1);
+        publish();
+    }
+    if (kt < nk) compute(As0, Bs0);
+
+    if constexpr (F == 16)
+        write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
+    else
+        write_tile_mfma32<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
+}
+
+}  // namespace ks

@@ -230,31 +230,16 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
 
     // epilogue
     if constexpr (CORE == CORE_FMA) {
+        write_tile(p, tc, Cb, [&](auto emit) {
 #pragma unroll
-        for (int i = 0; i < P1; ++i)
+            for (int i = 0; i < P1; ++i)
 #pragma unroll
-            for (int j = 0; j < P2; ++j)
-                store_entry(p, tc, Cb, row0 + subM + i, col0 + subN + j, accF[i][j]);
+                for (int j = 0; j < P2; ++j) emit(row0 + subM + i, col0 + subN + j, accF[i][j]);
+        });
     } else if constexpr (CORE == CORE_MFMA16) {
-        // accumulator register e of lane l holds C[4*(l/16) + e][l%16]
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    store_entry(p, tc, Cb, row0 + subM + i * 16 + 4 * (lane >> 4) + e,
-                                col0 + subN + j * 16 + (lane & 15), acc16[i][j][e]);
+        write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
     } else {
-        // accumulator register e of lane l holds C[8*(e/4) + 4*(l/32) + e%4][l%32]
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    store_entry(p, tc, Cb, row0 + subM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3),
-                                col0 + subN + j * 32 + (lane & 31), acc32[i][j][e]);
+        write_tile_mfma32<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
     }
 }
 

@@ -48,18 +48,68 @@ __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
     return c;
 }
 
-// One output entry.  splitK > 1: raw partial sum to the workspace slice of this split.
-__device__ __forceinline__ void store_entry(const GemmParams &p, const TileCoord &tc, float *Cb,
-                                            int row, int col, float acc) {
-    if (row >= p.M || col >= p.N) return;
+// Epilogue.  `visit(f)` calls f(row, col, acc) for every accumulator element this lane owns
+// (tile-relative to the matrix, i.e. absolute row / col).  The three output modes are separated
+// outside the element loops so the per-element code is a bounds test and one store:
+//   split-K: raw partial sum to this split's slice of the workspace;
+//   beta == 0: C = alpha * acc (C is never read);
+//   otherwise: C = alpha * acc + beta * C.
+template <class Visit>
+__device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord &tc, float *Cb,
+                                           Visit visit) {
+    const int M = p.M, N = p.N;
     if (p.splitK > 1) {
-        p.ws[(((long long)tc.split * p.batch + tc.batch) * p.M + row) * (long long)p.N + col] = acc;
+        float *w = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)M * N;
+        visit([&](int row, int col, float acc) {
+            if (row < M && col < N) w[(long long)row * N + col] = acc;
+        });
+    } else if (p.beta == 0.0f) {
+        const float alpha = p.alpha;
+        const long long ldc = p.ldc;
+        visit([&](int row, int col, float acc) {
+            if (row < M && col < N) Cb[(long long)row * ldc + col] = alpha * acc;
+        });
     } else {
-        float *c = Cb + (long long)row * p.ldc + col;
-        float v = p.alpha * acc;
-        if (p.beta != 0.0f) v = fmaf(p.beta, *c, v);
-        *c = v;
+        const float alpha = p.alpha, beta = p.beta;
+        const long long ldc = p.ldc;
+        visit([&](int row, int col, float acc) {
+            if (row < M && col < N) {
+                float *c = Cb + (long long)row * ldc + col;
+                *c = fmaf(beta, *c, alpha * acc);
+            }
+        });
     }
+}
+
+// accumulator register e of lane l of a 16x16 MFMA fragment holds C[4*(l/16) + e][l%16]
+template <int FM, int FN, class Acc>
+__device__ __forceinline__ void write_tile_mfma16(const GemmParams &p, const TileCoord &tc, float *Cb,
+                                                  int rowBase, int colBase, int lane, const Acc &acc) {
+    write_tile(p, tc, Cb, [&](auto emit) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    emit(rowBase + i * 16 + 4 * (lane >> 4) + e, colBase + j * 16 + (lane & 15), acc[i][j][e]);
+    });
+}
+
+// accumulator register e of lane l of a 32x32 MFMA fragment holds C[8*(e/4) + 4*(l/32) + e%4][l%32]
+template <int FM, int FN, class Acc>
+__device__ __forceinline__ void write_tile_mfma32(const GemmParams &p, const TileCoord &tc, float *Cb,
+                                                  int rowBase, int colBase, int lane, const Acc &acc) {
+    write_tile(p, tc, Cb, [&](auto emit) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    emit(rowBase + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3),
+                         colBase + j * 32 + (lane & 31), acc[i][j][e]);
+    });
 }
 
 }  // namespace ks

@@ -1,0 +1,172 @@
+"""Prune the kernel family and train the runtime selector from a timing table
+(paper Sections II-A, III, III-A, IV), then emit the deployed tree.
+
+    python -m paper_2003_06795_amd.tune.train --dtype f32 \
+        --timings paper_2003_06795_amd/tune/data/timings_f32_cfg2.csv --n-kept 8 --emit
+
+All arithmetic (normalisation, regression-tree pruning, scores, classifier fit, prediction) runs in
+the library's host tuner (ks_tune_*); this file only loads the CSV, splits it and writes results.
+Rows are split by SHAPE (the transposed variants of one shape stay together), 70/30, seeded.
+"""
+import argparse
+import csv
+import json
+import os
+import sys
+
+import numpy as np
+
+import workloads as wl
+from .. import binding as ks
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+DATA = os.path.join(HERE, "data")
+TABLE_INC = os.path.join(os.path.dirname(HERE), "csrc", "selector_table.inc")
+
+
+def load_table(path, dtype):
+    """-> (rows: list of dict(row, tA, tB, M, N, K, batch), T: seconds [rows x kernels])"""
+    nk = ks.num_kernels(ks.F32 if dtype == "f32" else ks.BF16)
+    cells, meta = {}, {}
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["dtype"] != dtype:
+                continue
+            key = (int(r["config"]), int(r["row"]))
+            meta[key] = dict(config=key[0], row=key[1], tA=int(r["transA"]), tB=int(r["transB"]),
+                             M=int(r["M"]), N=int(r["N"]), K=int(r["K"]), batch=int(r["batch"]))
+            cells.setdefault(key, {})[int(r["kernel"])] = float(r["median_ms"]) * 1e-3
+    keys = sorted(k for k in cells if len(cells[k]) == nk)
+    T = np.array([[cells[k][c] for c in range(nk)] for k in keys], dtype=np.float64)
+    return [meta[k] for k in keys], T
+
+
+def features_of(rows, n_features):
+    return np.stack([ks.features(r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"])[:n_features]
+                     for r in rows])
+
+
+def perf_of(rows, T):
+    flops = np.array([2.0 * r["M"] * r["N"] * r["K"] * r["batch"] for r in rows])
+    return flops[:, None] / T
+
+
+def split_config2(rows):
+    """Train/test masks by shape index (row // 4 in the config-2 table)."""
+    train, test = wl.config2_split()
+    shape_of = np.array([r["row"] // 4 for r in rows])
+    return np.isin(shape_of, train), np.isin(shape_of, test)
+
+
+def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted):
+    Ph = ks.tune_normalise(Ptr)
+    kept, reg = ks.tune_prune_tree(Xtr, Ph, n_kept)
+    w = None
+    if weighted:
+        # optional, not in the paper: weight a row by what a wrong choice inside the kept set can
+        # cost there (1 - worst/best normalised performance among kept configurations)
+        sub = Ph[:, kept]
+        w = 1.0 - sub.min(axis=1) / sub.max(axis=1) + 1e-3
+    tree = ks.tune_fit_selector(Xtr, Ptr, kept, max_depth=max_depth,
+                                min_samples_leaf=min_samples_leaf, row_weight=w)
+    return kept, reg, tree
+
+
+def evaluate(tree, kept, X, P):
+    Ph = ks.tune_normalise(P)
+    chosen = ks.tune_predict(tree, X)
+    return dict(achievable=ks.tune_achievable(Ph, kept), selector=ks.tune_selector_score(Ph, chosen),
+                best_single=max(ks.tune_achievable(Ph, [c]) for c in range(P.shape[1])))
+
+
+def emit_table(trees):
+    """trees: {'f32': structured array, 'bf16': structured array} -> csrc/selector_table.inc"""
+    lines = [
+        "// Deployed decision trees (paper Section IV), one per operand type.",
+        "// Written by paper_2003_06795_amd/tune/train.py from a measured timing table; do not edit.",
+        "// {feature, left, right, value, threshold}: feature < 0 is a leaf choosing kernel `value`;",
+        "// otherwise go left when features[feature] <= threshold.",
+    ]
+    for dtype, name in (("f32", "kTreeF32"), ("bf16", "kTreeBf16")):
+        lines.append("static const ks_tree_node_t %s[] = {" % name)
+        for n in trees[dtype]:
+            lines.append("    {%d, %d, %d, %d, %dLL}," % (n["feature"], n["left"], n["right"], n["value"],
+                                                          n["threshold"]))
+        lines.append("};")
+    with open(TABLE_INC, "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
+def tree_to_json(tree):
+    return [[int(n["feature"]), int(n["left"]), int(n["right"]), int(n["value"]), int(n["threshold"])]
+            for n in tree]
+
+
+def tree_from_json(rows):
+    t = np.zeros(len(rows), dtype=ks.TREE_DTYPE)
+    for i, r in enumerate(rows):
+        t[i] = tuple(r)
+    return t
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--timings", required=True)
+    ap.add_argument("--n-kept", type=int, default=8)
+    ap.add_argument("--max-depth", type=int, default=12)
+    ap.add_argument("--min-samples-leaf", type=int, default=1)
+    ap.add_argument("--features", type=int, default=ks.NUM_RAW_FEATURES,
+                    help="length of the feature prefix (6 = raw sizes and flags, 10 = with derived)")
+    ap.add_argument("--weighted", action="store_true")
+    ap.add_argument("--all-rows", action="store_true", help="train on every row (no held-out set)")
+    ap.add_argument("--emit", action="store_true", help="write tree JSON + csrc/selector_table.inc")
+    ap.add_argument("--report", default=None)
+    a = ap.parse_args(argv)
+
+    rows, T = load_table(a.timings, a.dtype)
+    P = perf_of(rows, T)
+    X = features_of(rows, a.features)
+    if a.all_rows:
+        tr = te = np.ones(len(rows), dtype=bool)
+    else:
+        tr, te = split_config2(rows)
+    report = dict(dtype=a.dtype, timings=os.path.relpath(a.timings), rows=len(rows),
+                  train_rows=int(tr.sum()), test_rows=int(te.sum()), features=a.features,
+                  max_depth=a.max_depth, min_samples_leaf=a.min_samples_leaf, weighted=a.weighted,
+                  sweep=[])
+    chosen_fit = None
+    for n in sorted({4, 5, 6, 8, 15, a.n_kept}):
+        kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted)
+        ev_tr, ev_te = evaluate(tree, kept, X[tr], P[tr]), evaluate(tree, kept, X[te], P[te])
+        report["sweep"].append(dict(n_kept=n, kept=kept.tolist(), tree_nodes=len(tree), train=ev_tr, test=ev_te))
+        print("N=%2d kept=%-40s nodes=%3d | train achievable %.4f selector %.4f | test achievable %.4f "
+              "selector %.4f (best single %.4f)" % (n, kept.tolist(), len(tree), ev_tr["achievable"],
+                                                    ev_tr["selector"], ev_te["achievable"],
+                                                    ev_te["selector"], ev_te["best_single"]))
+        if n == a.n_kept:
+            chosen_fit = (kept, reg, tree)
+    kept, reg, tree = chosen_fit
+    report["deployed"] = dict(n_kept=a.n_kept, kept=kept.tolist(), tree=tree_to_json(tree),
+                              pruning_tree=tree_to_json(reg))
+    if a.emit:
+        os.makedirs(DATA, exist_ok=True)
+        with open(os.path.join(DATA, "tree_%s.json" % a.dtype), "w") as f:
+            json.dump(report, f, indent=1)
+        trees = {}
+        for dt, default in (("f32", 35), ("bf16", 5)):
+            p = os.path.join(DATA, "tree_%s.json" % dt)
+            if os.path.exists(p):
+                trees[dt] = tree_from_json(json.load(open(p))["deployed"]["tree"])
+            else:
+                trees[dt] = tree_from_json([[-1, -1, -1, default, 0]])
+        emit_table(trees)
+        print("wrote %s (rebuild the library to deploy it)" % os.path.relpath(TABLE_INC))
+    if a.report:
+        with open(a.report, "w") as f:
+            json.dump(report, f, indent=1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -110,6 +110,8 @@ def test_f32_permutation_operand_moves_rows_bit_exact(gpu, tA, tB):
 
 
 SHAPES_BF16 = [
+    (264, 136, 384, 2, (8, 16, 4), (8, 0, 0)),      # K a multiple of every K-step: direct-to-LDS path
+    (520, 264, 256, 1, (0, 0, 0), (0, 0, 0)),       # several 256-wide tiles on the direct-to-LDS path
     (264, 136, 200, 2, (0, 0, 0), (0, 0, 0)),       # multiples of 8: 16-byte path
     (261, 131, 203, 2, (3, 1, 2), (5, 3, 7)),       # ragged: scalar path
     (40, 520, 72, 1, (8, 8, 4), (0, 0, 0)),
@@ -136,15 +138,37 @@ def test_bf16_all_kernels_within_tolerance(gpu, shape, tA, tB):
 
 
 @pytest.mark.parametrize("tA,tB", LAYOUTS)
-def test_bf16_small_integers_bit_exact(gpu, tA, tB):
-    p = wl.make_problem("bf16", tA, tB, 150, 170, 330, batch=2, alpha=1.0, beta=0.0, seed=6,
-                        key=tA * 2 + tB, dist="ints", c_fill="nan", pad=(1, 0, 3))
+@pytest.mark.parametrize("shape", [(150, 170, 330, (1, 0, 3)), (152, 168, 384, (0, 8, 3))])
+def test_bf16_small_integers_bit_exact(gpu, shape, tA, tB):
+    """The second shape takes the direct-to-LDS path (aligned, K a multiple of every K-step)."""
+    M, N, K, pad = shape
+    p = wl.make_problem("bf16", tA, tB, M, N, K, batch=2, alpha=1.0, beta=0.0, seed=6,
+                        key=tA * 2 + tB, dist="ints", c_fill="nan", pad=pad)
     dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
     live = ~c_padding_mask(p)
     for kid in ids_of(gpu, "bf16"):
         prep_workspace(gpu, p, kid)
         got = dp.run(kid)
         assert np.array_equal(got[live], ref[live]), "kernel %d" % kid
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+def test_bf16_generic_and_direct_to_lds_paths_agree_bitwise(gpu, tA, tB):
+    """Same tiles, same summation order: the two code paths of an instantiation give equal bits."""
+    import paper_2003_06795_amd.binding as ks
+    p = wl.make_problem("bf16", tA, tB, 392, 264, 512, batch=1, alpha=1.0, beta=0.5, seed=8,
+                        key=tA * 2 + tB, dist="normal")
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    for kid in ids_of(gpu, "bf16"):
+        prep_workspace(gpu, p, kid)
+        fast = dp.run(kid)
+        try:
+            ks.set_fast_path(False)
+            slow = dp.run(kid)
+        finally:
+            ks.set_fast_path(True)
+        check(p, fast, ref, "bf16 kernel %d direct-to-LDS" % kid)
+        assert np.array_equal(fast, slow), "kernel %d" % kid
 
 
 # ----------------------------------------------------------------------------- conventions and edges
