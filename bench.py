@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"f32": 157.3, "bf16": 2516.6}      # dense matrix-core TFLOP/s of MI355X
 HBM_PEAK_GBS = 8000.0
+CALIB_BYTES = 256 * 1024 * 1024
 
 
 def kernel_symbol(ks, dt, kid, tA, tB, vec=True):
@@ -75,19 +76,32 @@ def allocate(rows, torch):
     return bufs
 
 
-def run_pass(ks, rows, bufs, torch, events=None, reps=None):
-    """One pass: every row's GEMM, launched reps[i] times back to back between its event pair."""
+def run_pass(ks, rows, bufs, reps, stream, out_ms=None):
+    """One pass: every row's GEMM with the selected kernel (kernel id -1 = ks_select), launched
+    reps[i] times back to back inside the library between one HIP event pair (ks_time_gemm, the
+    tuner's own clock).  out_ms[i] receives the per-launch milliseconds."""
     for i, r in enumerate(rows):
         A, B, C = bufs[(r["dtype"], r["shape"])]
         M, N, K, b = r["M"], r["N"], r["K"], r["batch"]
-        fn = ks.gemm_f32 if r["dtype"] == "f32" else ks.gemm_bf16
-        if events is not None:
-            events[i][0].record()
-        for _ in range(1 if reps is None else reps[i]):
-            fn(r["tA"], r["tB"], M, N, K, r["alpha"], A, M if r["tA"] else K, B, K if r["tB"] else N,
-               r["beta"], C, N, b, M * K if b > 1 else 0, K * N if b > 1 else 0, M * N if b > 1 else 0)
-        if events is not None:
-            events[i][1].record()
+        ms = ks.time_gemm(ks.F32 if r["dtype"] == "f32" else ks.BF16, -1, r["tA"], r["tB"], M, N, K,
+                          r["alpha"], A, M if r["tA"] else K, B, K if r["tB"] else N, r["beta"], C, N, b,
+                          M * K if b > 1 else 0, K * N if b > 1 else 0, M * N if b > 1 else 0,
+                          stream=stream, warmup=0, iters=1, reps=reps[i])
+        if out_ms is not None:
+            out_ms[i] = ms[0]
+
+
+def stored_traffic(workload, symbol):
+    """HBM bytes per launch of `symbol` from the committed counter summary (two rocprofv3 --pmc runs
+    of this script, FETCH_SIZE and WRITE_SIZE, scaled by the calibration copy), or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for k in json.load(open(path)).get("kernels", []):
+        if k["kernel"] == symbol:
+            return dict(fetch_bytes=k["fetch_bytes"], write_bytes=k["write_bytes"],
+                        total_bytes=k["fetch_bytes"] + k["write_bytes"], algorithmic_bytes=k.get("algorithmic_bytes"))
+    return None
 
 
 def cpu_baseline(rows, budget_s=15.0):
@@ -129,6 +143,7 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the bf16 large-shape report")
+    ap.add_argument("--dump-rows", default=None, help="write per-row kernel id, time and TFLOP/s as CSV")
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md); "
@@ -137,6 +152,12 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs an MI355X (no CPU fallback exists)")
     import paper_2003_06795_amd.binding as ks
+
+    # yardstick for hardware traffic counters: one plain copy of CALIB_BYTES, outside the timed region
+    calib = torch.rand(2 * CALIB_BYTES // 4, device="cuda")
+    ks.calibration_copy(calib[CALIB_BYTES // 4:], calib[:CALIB_BYTES // 4], CALIB_BYTES)
+    torch.cuda.synchronize()
+    del calib
 
     rows = build_rows(a.workload)
     dtype = rows[0]["dtype"]
@@ -149,24 +170,22 @@ def main():
         ws = torch.empty(need // 4 + 1, dtype=torch.float32, device="cuda")
         ks.set_workspace(ws)
 
-    # Like the tuner, a row's sample is a short run of back-to-back launches so that the event
-    # interval measures kernel time rather than the gap between two dependent packets.  The
+    # Like the tuner, a row's sample is a short run of back-to-back launches (issued natively by
+    # ks_time_gemm) so that the event interval measures kernel time rather than host dispatch.  The
     # repetition count is a fixed function of the row's flops (about 3e8 flops per sample, at
     # most 16 launches), so warm-up and timed passes launch exactly the same kernels.
     reps = [int(min(16, max(1, np.ceil(3e8 / (2.0 * r["M"] * r["N"] * r["K"] * r["batch"]))))) for r in rows]
+    stream = torch.cuda.current_stream().cuda_stream
     for _ in range(a.warmup):
-        run_pass(ks, rows, bufs, torch, None, reps)
-    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in rows] for _ in range(a.steps)]
+        run_pass(ks, rows, bufs, reps, stream)
+    ms = np.zeros((a.steps, len(rows)))          # per-launch milliseconds, steps x rows
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(a.steps):
-        run_pass(ks, rows, bufs, torch, events[s], reps)
+        run_pass(ks, rows, bufs, reps, stream, ms[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    # per-launch milliseconds, steps x rows
-    ms = np.array([[e0.elapsed_time(e1) for (e0, e1) in step] for step in events]) / np.array(reps)[None, :]
     med = np.median(ms, axis=0)
     flops = np.array([2.0 * r["M"] * r["N"] * r["K"] * r["batch"] for r in rows])
     tflops = flops / (med * 1e-3) / 1e12
@@ -174,6 +193,12 @@ def main():
 
     # dominant kernel symbol: the instantiation with the most device time in a step
     chosen = [ks.select(dt, r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"]) for r in rows]
+    if a.dump_rows:
+        with open(a.dump_rows, "w") as f:
+            f.write("row,transA,transB,M,N,K,kernel,reps,median_ms,tflops\n")
+            for i, r in enumerate(rows):
+                f.write("%d,%d,%d,%d,%d,%d,%d,%d,%.6g,%.6g\n" % (i, r["tA"], r["tB"], r["M"], r["N"], r["K"],
+                                                               chosen[i], reps[i], med[i], tflops[i]))
     sym = [kernel_symbol(ks, dt, k, r["tA"], r["tB"]) for k, r in zip(chosen, rows)]
     by = {}
     for i, s in enumerate(sym):
@@ -189,7 +214,7 @@ def main():
     d = by[dom]
     achieved = d["flops"] / d["time"] / 1e12
     roofline = dict(bound="mfma", kernel=dom, achieved=achieved, peak=PEAK[dtype], unit="TFLOP/s",
-                    frac=achieved / PEAK[dtype], traffic=None, launches_per_step=d["launches"] // a.steps,
+                    frac=achieved / PEAK[dtype], traffic=stored_traffic(a.workload, dom), launches_per_step=d["launches"] // a.steps,
                     avg_launch_us=d["time"] / d["launches"] * 1e6,
                     share_of_step_time=d["time"] / float((ms * np.array(reps)[None, :]).sum() * 1e-3),
                     algorithmic_gbs=d["bytes"] / d["time"] / 1e9)
@@ -204,7 +229,7 @@ def main():
                                 "bf16 large/skinny set: 7 shapes x {NN,NT}, selected kernel per row"),
                    "rows": len(rows), "kernels_used": len(set(chosen)),
                    "launches_per_step": int(sum(reps)),
-                   "timing": "per row: median over steps of (HIP-event interval around reps back-to-back launches) / reps"},
+                   "timing": "per row: median over steps of (HIP-event interval around reps back-to-back launches inside ks_time_gemm) / reps"},
         "device_ms_per_step": float((ms * np.array(reps)[None, :]).sum() / a.steps),
         "best_row_tflops": float(tflops.max()),
         "roofline": roofline,

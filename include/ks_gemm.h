@@ -152,6 +152,11 @@ int ks_get_selector(int dtype, ks_tree_node_t *nodes, int cap);
  * the generic path (for testing it at aligned shapes); nonzero restores the default. */
 int ks_set_fast_path(int enabled);
 
+/* Measurement aid: copies `bytes` (a multiple of 16; both device pointers 16-byte aligned) with a
+ * plain one-read-one-write kernel (ks::copy_kernel).  Hardware traffic counters collected over a
+ * profile that contains this launch are scaled by what they report for it. */
+int ks_calibration_copy(void *dst_device, const void *src_device, size_t bytes, void *stream);
+
 /* ---------------------------------------------------------------- workspace
  * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no
  * atomics) need split_k * batch * M * N floats of scratch.  The caller registers one device

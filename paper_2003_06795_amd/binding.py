@@ -53,7 +53,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
-    "ks_time_gemm", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
+    "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_status_string",
@@ -79,6 +79,7 @@ def lib():
     L.ks_features.argtypes = [_i64, _i64, _i64, _i64, _i, _i, _p]
     L.ks_set_selector.argtypes = [_i, _p, _i]
     L.ks_get_selector.argtypes = [_i, _p, _i]
+    L.ks_calibration_copy.argtypes = [_p, _p, ctypes.c_size_t, _p]
     L.ks_set_fast_path.argtypes = [_i]
     L.ks_set_workspace.argtypes = [_p, ctypes.c_size_t]
     L.ks_workspace_bytes_needed.argtypes = [_i, _i, _i64, _i64, _i64]
@@ -214,6 +215,10 @@ def get_selector(dtype):
     if n < 0:
         raise KsError(n, "ks_get_selector")
     return a[:n].copy()
+
+
+def calibration_copy(dst, src, nbytes, stream=None):
+    _check(lib().ks_calibration_copy(_dev(dst), _dev(src), int(nbytes), _stream(stream)), "ks_calibration_copy")
 
 
 def set_fast_path(enabled):

@@ -27,17 +27,17 @@ constexpr int KS_CORE_OF_FMA = KS_CORE_FMA, KS_CORE_OF_MFMA16 = KS_CORE_MFMA16,
               KS_CORE_OF_MFMA32 = KS_CORE_MFMA32;
 
 const InstanceDesc kF32[kNumF32] = {
-#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2)                                      \
-    {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), 1, \
+#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK)                              \
+    {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), SPLITK, \
      2 * BK * ((BM + 4) + (BN + 4)) * 4},
 #include "instances.def"
 #undef KS_F32_INSTANCE
 };
 
 const InstanceDesc kBf16[kNumBf16] = {
-#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, SPLITK)                                   \
+#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK)                           \
     {id, (F) == 16 ? KS_CORE_MFMA16 : KS_CORE_MFMA32, BM, BN, BK, WM, WN, 64 * (BM / WM) * (BN / WN), \
-     SPLITK, 2 * BK * (BM + BN) * 2},
+     SPLITK, STAGES * BK * (BM + BN) * 2},
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 };
@@ -90,6 +90,14 @@ __global__ void scale_c_kernel(float *C, long long ldc, long long strideC, int M
         float *c = C + b * strideC + (r / N) * ldc + (r % N);
         *c = beta == 0.0f ? 0.0f : beta * *c;
     }
+}
+
+// Plain 16-byte-per-lane copy of known size: the yardstick that hardware traffic counters
+// (rocprofv3 FETCH_SIZE / WRITE_SIZE) are scaled by.
+__global__ void copy_kernel(const floatx4 *src, floatx4 *dst, long long n16) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n16;
+         i += (long long)gridDim.x * blockDim.x)
+        dst[i] = src[i];
 }
 
 // Split-K second pass: C = alpha * (ws[0] + ws[1] + ... in this fixed order) + beta * C
@@ -230,6 +238,17 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     return KS_OK;
 }
 
+extern "C" int ks_calibration_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0) return KS_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16)
+        return KS_ERR_INVALID_ARG;
+    const long long n16 = (long long)(bytes / 16);
+    const int grid = (int)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
+    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const floatx4 *>(src), static_cast<floatx4 *>(dst), n16);
+    return hipGetLastError() == hipSuccess ? KS_OK : KS_ERR_LAUNCH;
+}
+
 extern "C" int ks_set_fast_path(int enabled) {
     g_forceGeneric = enabled ? 0 : 1;
     return KS_OK;
@@ -307,23 +326,27 @@ extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, in
         if (kernel_id < 0) return kernel_id;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // the first call also proves the arguments: nothing is timed if it fails
-    int rc = run(dtype, kernel_id, KS_GEMM_PASS);
-    if (rc != KS_OK) return rc;
-    for (int i = 1; i < warmup; ++i) run(dtype, kernel_id, KS_GEMM_PASS);
     static hipEvent_t ev[2 * 1024];
     static int evCount = 0;
     while (evCount < 2 * iters) {
         if (hipEventCreate(&ev[evCount]) != hipSuccess) return KS_ERR_LAUNCH;
         ++evCount;
     }
+    // the first launch also proves the arguments: if it is refused nothing else is enqueued
+    int rc = KS_OK;
+    for (int i = 0; i < warmup; ++i) {
+        rc = run(dtype, kernel_id, KS_GEMM_PASS);
+        if (rc != KS_OK) return rc;
+    }
     for (int i = 0; i < iters; ++i) {
-        hipEventRecord(ev[2 * i], s);
-        for (int r = 0; r < reps; ++r) rc |= run(dtype, kernel_id, KS_GEMM_PASS);
-        hipEventRecord(ev[2 * i + 1], s);
+        if (hipEventRecord(ev[2 * i], s) != hipSuccess) return KS_ERR_LAUNCH;
+        for (int r = 0; r < reps; ++r) {
+            rc = run(dtype, kernel_id, KS_GEMM_PASS);
+            if (rc != KS_OK) return rc;
+        }
+        if (hipEventRecord(ev[2 * i + 1], s) != hipSuccess) return KS_ERR_LAUNCH;
     }
     if (hipStreamSynchronize(s) != hipSuccess) return KS_ERR_LAUNCH;
-    if (rc != KS_OK) return KS_ERR_LAUNCH;
     for (int i = 0; i < iters; ++i) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess) return KS_ERR_LAUNCH;

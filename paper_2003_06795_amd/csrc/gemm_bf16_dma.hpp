@@ -20,6 +20,8 @@
 // A direct-to-LDS load writes LDS_base(wave-uniform) + lane * 16, i.e. one instruction fills 1 KiB
 // of the tile; the swizzle is applied by choosing which global chunk each lane fetches.
 #pragma once
+#include <type_traits>
+
 #include "gemm_bf16.hpp"
 
 namespace ks {
@@ -85,17 +87,46 @@ struct DmaPlan {
     }
 };
 
-template <int F, int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC>
+// vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Scheduling hint for one k-substep: NM MFMAs with NR LDS reads spread evenly between them.
+template <int M, int NM, int NR>
+struct InterleaveHint {
+    __device__ __forceinline__ static void emit() {
+        if constexpr (M < NM) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
+            // all reads go behind the first NM-2 MFMAs; the last two cover the read latency
+            constexpr int SLOTS = NM > 2 ? NM - 2 : 1;
+            constexpr int reads = M < SLOTS ? (NR * (M + 1)) / SLOTS - (NR * M) / SLOTS : 0;
+            if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);   // LDS reads
+            InterleaveHint<M + 1, NM, NR>::emit();
+        }
+    }
+};
+
+template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool AKC, bool BKC>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kernel(const GemmParams p) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int FM = WM / F, FN = WN / F;
     constexpr int KSTEP = F == 32 ? 16 : 32;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static_assert(STAGES >= 2 && STAGES <= 4, "stages");
     using LK = Bf16Lds<BK>;
+    // one __shared__ object per stage: the compiler can then tell that the stage being filled by
+    // the in-flight loads is not the stage the ds_reads touch, and does not serialise them
     __shared__ __attribute__((aligned(1024))) char As0[A_BYTES];
     __shared__ __attribute__((aligned(1024))) char As1[A_BYTES];
+    __shared__ __attribute__((aligned(1024))) char As2[STAGES > 2 ? A_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char As3[STAGES > 3 ? A_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) char Bs0[B_BYTES];
     __shared__ __attribute__((aligned(1024))) char Bs1[B_BYTES];
+    __shared__ __attribute__((aligned(1024))) char Bs2[STAGES > 2 ? B_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char Bs3[STAGES > 3 ? B_BYTES : 16];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const TileCoord tc = tile_of_block(p);
@@ -137,85 +168,112 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
                 for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
         }
 
+    // LDS -> register fragments of one k-substep (KSTEP values of k) for this wave's tile
+    auto load_frags = [&](const char *as, const char *bs, int kk, bf16x8 (&a)[FM], bf16x8 (&b)[FN]) {
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            if constexpr (AKC) {
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
+                    as + 16 * LK::chunk(subM + i * F + lrow, kk / 8 + lgrp)));
+            } else {
+                using LT = Bf16LdsT<BM>;
+                const int kb = kk + 8 * lgrp + trK;
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb, subM + i * F + trRow)));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb + 4, subM + i * F + trRow)));
+                const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                a[i] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            if constexpr (BKC) {
+                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
+                    bs + 16 * LK::chunk(subN + j * F + lrow, kk / 8 + lgrp)));
+            } else {
+                using LT = Bf16LdsT<BN>;
+                const int kb = kk + 8 * lgrp + trK;
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb, subN + j * F + trRow)));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb + 4, subN + j * F + trRow)));
+                const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                b[j] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+    };
+
+    // One K-step on a landed stage.  The fragments of k-substep s+1 are fetched while the MFMAs of
+    // substep s run (two register sets), and the scheduler is told to issue one LDS read after
+    // every MFMA instead of batching reads behind a wait.
+    constexpr int NSUB = BK / KSTEP;
+    constexpr int NREAD = (AKC ? FM : 2 * FM) + (BKC ? FN : 2 * FN);   // LDS reads per substep
+    constexpr int NMFMA = FM * FN;
     auto compute = [&](const char *as, const char *bs) {
+        bf16x8 a[2][FM], b[2][FN];
+        load_frags(as, bs, 0, a[0], b[0]);
+        __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += KSTEP) {
-            bf16x8 a[FM], b[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                if constexpr (AKC) {
-                    a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
-                        as + 16 * LK::chunk(subM + i * F + lrow, kk / 8 + lgrp)));
-                } else {
-                    using LT = Bf16LdsT<BM>;
-                    const int kb = kk + 8 * lgrp + trK;
-                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb, subM + i * F + trRow)));
-                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb + 4, subM + i * F + trRow)));
-                    typedef short shortx8 __attribute__((ext_vector_type(8)));
-                    const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    a[i] = __builtin_bit_cast(bf16x8, v);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                if constexpr (BKC) {
-                    b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
-                        bs + 16 * LK::chunk(subN + j * F + lrow, kk / 8 + lgrp)));
-                } else {
-                    using LT = Bf16LdsT<BN>;
-                    const int kb = kk + 8 * lgrp + trK;
-                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb, subN + j * F + trRow)));
-                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb + 4, subN + j * F + trRow)));
-                    typedef short shortx8 __attribute__((ext_vector_type(8)));
-                    const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    b[j] = __builtin_bit_cast(bf16x8, v);
-                }
-            }
+        for (int sub = 0; sub < NSUB; ++sub) {
+            const int cur = sub & 1;
+            if (sub + 1 < NSUB) load_frags(as, bs, (sub + 1) * KSTEP, a[cur ^ 1], b[cur ^ 1]);
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     if constexpr (F == 16)
-                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc16[i][j], 0, 0, 0);
+                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[cur][i], b[cur][j], acc16[i][j], 0, 0, 0);
                     else
-                        acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc32[i][j], 0, 0, 0);
+                        acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc32[i][j], 0, 0, 0);
                 }
+            if (sub + 1 < NSUB) InterleaveHint<0, NMFMA, NREAD>::emit();
+            else InterleaveHint<0, NMFMA, 0>::emit();
         }
     };
 
-    // every wave waits for its own direct-to-LDS loads before the barrier publishes the stage
-    auto publish = [&]() {
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), other counters untouched
+    // Software pipeline over K-steps with a ring of STAGES LDS stages.  K-step t lives in stage
+    // t % STAGES.  Before computing step t a wave waits until at most the loads of the younger
+    // steps (t+1 .. t+STAGES-2) are still in flight, i.e. its own part of step t has landed; the
+    // barrier then (a) publishes every wave's part of step t and (b) proves that everyone has
+    // finished reading step t-1, whose stage is refilled right away with step t+STAGES-1.
+    constexpr int LOADS = DmaPlan<BM, BK, NW, AKC>::PER_WAVE + DmaPlan<BN, BK, NW, BKC>::PER_WAVE;
+    static_assert((STAGES - 2) * LOADS < 64, "vmcnt range");
+    auto issue = [&](int t, auto stage) {
+        constexpr int S = decltype(stage)::value;
+        char *as = S == 0 ? As0 : S == 1 ? As1 : S == 2 ? As2 : As3;
+        char *bs = S == 0 ? Bs0 : S == 1 ? Bs1 : S == 2 ? Bs2 : Bs3;
+        pa.issue(aTile + t * aStep, as, wave);
+        pb.issue(bTile + t * bStep, bs, wave);
+    };
+    auto step = [&](int t, auto stage) {
+        constexpr int S = decltype(stage)::value;
+        const int younger = min(nk - 1 - t, STAGES - 2);     // steps after t whose loads were issued
+        if (younger >= 2) wait_vmcnt<(STAGES > 3 ? 2 : 0) * LOADS>();
+        else if (younger == 1) wait_vmcnt<(STAGES > 2 ? 1 : 0) * LOADS>();
+        else wait_vmcnt<0>();
         __syncthreads();
+        if (t + STAGES - 1 < nk) issue(t + STAGES - 1, std::integral_constant<int, (S + STAGES - 1) % STAGES>{});
+        __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the MFMAs they overlap
+        const char *as = S == 0 ? As0 : S == 1 ? As1 : S == 2 ? As2 : As3;
+        const char *bs = S == 0 ? Bs0 : S == 1 ? Bs1 : S == 2 ? Bs2 : Bs3;
+        compute(as, bs);
     };
 
-    if (nk > 0) {
-        pa.issue(aTile, As0, wave);
-        pb.issue(bTile, Bs0, wave);
+    if (nk > 0) issue(0, std::integral_constant<int, 0>{});
+    if (STAGES > 2 && nk > 1) issue(1, std::integral_constant<int, 1>{});
+    if (STAGES > 3 && nk > 2) issue(2, std::integral_constant<int, 2>{});
+    int t = 0;
+    for (; t + STAGES <= nk; t += STAGES) {
+        step(t, std::integral_constant<int, 0>{});
+        step(t + 1, std::integral_constant<int, 1>{});
+        if constexpr (STAGES > 2) step(t + 2, std::integral_constant<int, 2>{});
+        if constexpr (STAGES > 3) step(t + 3, std::integral_constant<int, 3>{});
     }
-    publish();
-    // two K-steps per trip so that the stage being filled and the stage being read are different
-    // __shared__ objects
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-        pa.issue(aTile + (kt + 1) * aStep, As1, wave);
-        pb.issue(bTile + (kt + 1) * bStep, Bs1, wave);
-        __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the MFMAs they overlap
-        compute(As0, Bs0);
-        publish();
-        if (kt + 2 < nk) {
-            pa.issue(aTile + (kt + 2) * aStep, As0, wave);
-            pb.issue(bTile + (kt + 2) * bStep, Bs0, wave);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        compute(As1, Bs1);
-        publish();
-    }
-    if (kt < nk) compute(As0, Bs0);
+    if (t < nk) step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < nk) step(t + 1, std::integral_constant<int, 1>{});
+    if constexpr (STAGES > 2) { if (t + 2 < nk) step(t + 2, std::integral_constant<int, 2>{}); }
 
     if constexpr (F == 16)
         write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);

@@ -30,7 +30,7 @@ static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t 
 
 template <int SHARD>
 static void fill(LaunchFn *table) {
-#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, SPLITK) \
+#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
     if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16<F, BM, BN, BK, WM, WN>;
 #include "instances.def"
 #undef KS_BF16_INSTANCE

@@ -31,7 +31,7 @@ static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s
 
 template <int SHARD>
 static void fill(LaunchFn *table) {
-#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2) \
+#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) \
     if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2>;
 #include "instances.def"
 #undef KS_F32_INSTANCE

@@ -12,7 +12,7 @@ struct InstanceDesc {
 };
 
 constexpr int kNumF32 = 64;
-constexpr int kNumBf16 = 24;
+constexpr int kNumBf16 = 32;
 constexpr int kShards = 16;
 
 }  // namespace ks

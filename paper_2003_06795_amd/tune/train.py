@@ -51,11 +51,22 @@ def perf_of(rows, T):
     return flops[:, None] / T
 
 
-def split_config2(rows):
-    """Train/test masks by shape index (row // 4 in the config-2 table)."""
-    train, test = wl.config2_split()
-    shape_of = np.array([r["row"] // 4 for r in rows])
-    return np.isin(shape_of, train), np.isin(shape_of, test)
+def split_rows(rows):
+    """Train/test masks by SHAPE.  Config 2 (fp32 tuning set, 4 layouts per shape) and config 6
+    (bf16 tuning set, 2 layouts per shape) are split 70/30 with their seeded permutation; rows of
+    any other configuration in the table (e.g. the named bf16 large/skinny cells) are training
+    rows only."""
+    tr = np.zeros(len(rows), dtype=bool)
+    te = np.zeros(len(rows), dtype=bool)
+    s2, s6 = wl.config2_split(), wl.bf16_tuning_split()
+    for i, r in enumerate(rows):
+        if r["config"] == 2:
+            tr[i], te[i] = r["row"] // 4 in s2[0], r["row"] // 4 in s2[1]
+        elif r["config"] == 6:
+            tr[i], te[i] = r["row"] // 2 in s6[0], r["row"] // 2 in s6[1]
+        else:
+            tr[i] = True
+    return tr, te
 
 
 def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted):
@@ -130,7 +141,7 @@ def main(argv=None):
     if a.all_rows:
         tr = te = np.ones(len(rows), dtype=bool)
     else:
-        tr, te = split_config2(rows)
+        tr, te = split_rows(rows)
     report = dict(dtype=a.dtype, timings=os.path.relpath(a.timings), rows=len(rows),
                   train_rows=int(tr.sum()), test_rows=int(te.sum()), features=a.features,
                   max_depth=a.max_depth, min_samples_leaf=a.min_samples_leaf, weighted=a.weighted,

@@ -76,6 +76,7 @@ def test_f32_all_kernels_within_tolerance(gpu, shape, tA, tB):
                         key=M + 2 * tA + tB, pad=pad, batch_pad=bpad)
     dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
     for kid in ids_of(gpu, "f32"):
+        prep_workspace(gpu, p, kid)
         check(p, dp.run(kid), ref, "f32 kernel %d %s tA=%d tB=%d" % (kid, shape[:3], tA, tB))
 
 
@@ -88,6 +89,7 @@ def test_f32_small_integers_bit_exact(gpu, tA, tB):
     dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
     live = ~c_padding_mask(p)
     for kid in ids_of(gpu, "f32"):
+        prep_workspace(gpu, p, kid)
         got = dp.run(kid)
         assert np.array_equal(got[live], ref[live]), "kernel %d" % kid
 
@@ -106,6 +108,7 @@ def test_f32_permutation_operand_moves_rows_bit_exact(gpu, tA, tB):
     p.B = np.ascontiguousarray(X.T if tB else X).ravel()
     dp = gpu.DeviceProblem(p)
     for kid in ids_of(gpu, "f32"):
+        prep_workspace(gpu, p, kid)
         assert np.array_equal(dp.run(kid).reshape(M, N), X[perm, :]), "kernel %d" % kid
 
 

@@ -18,7 +18,8 @@ import numpy as np
 __all__ = [
     "Problem", "make_problem", "uniform_pm1", "normal_scaled", "f32_to_bf16_rne",
     "bf16_to_f32", "config1_problem", "CONFIG1_TILES", "config2_shapes", "config2_split",
-    "config2_rows", "config3_shapes", "config4_shapes", "config5_shapes",
+    "config2_rows", "config3_shapes", "config4_shapes", "config5_shapes", "bf16_tuning_shapes",
+    "bf16_tuning_split",
 ]
 
 
@@ -227,3 +228,28 @@ def config5_shapes():
 
 
 CONFIG5_LAYOUTS = [(0, 0), (0, 1)]
+
+
+# --------------------------------------------------------------------------- bf16 tuning set
+
+def bf16_tuning_shapes(n=160, seed=5, lo=64, hi=16384, max_mnk=2 ** 39):
+    """(M, N, K) triples for tuning the bf16 family: each dimension log-uniform in [lo, hi],
+    M and N rounded to multiples of 64 and K to a multiple of 128 (the sizes transformer-style
+    layers produce); triples with M*N*K above max_mnk are redrawn.  Each is run as NN and NT."""
+    r = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        dims = []
+        for d in range(3):
+            mult = 128 if d == 2 else 64
+            v = float(np.exp(r.uniform(np.log(lo), np.log(hi))))
+            dims.append(min(max(int(round(v / mult)) * mult, mult), hi))
+        if dims[0] * dims[1] * dims[2] <= max_mnk:
+            out.append(tuple(dims))
+    return out
+
+
+def bf16_tuning_split(n=160, seed=5, train_fraction=0.7):
+    perm = np.random.default_rng([seed, 0x5917]).permutation(n)
+    n_train = int(round(train_fraction * n))
+    return sorted(int(i) for i in perm[:n_train]), sorted(int(i) for i in perm[n_train:])
