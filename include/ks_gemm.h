@@ -84,7 +84,9 @@ typedef struct {
 /* ---------------------------------------------------------------- GEMM (Section II)
  * C_b = alpha * op(A_b) * op(B_b) + beta * C_b for b in [0, batch).
  * ks_gemm_* picks the kernel with ks_select (Section IV) and is bit-identical to
- * ks_gemm_*_with_kernel(ks_select(...), ...).  A, B, C: device pointers.
+ * ks_gemm_*_with_kernel(ks_select(...), ...) whenever the registered workspace can hold the
+ * chosen kernel's split-K partial sums; if it cannot (or none is registered) the instance with
+ * the same tiles and split_k == 1 runs instead.  A, B, C: device pointers.
  * bf16 operands are raw bfloat16 bit patterns; accumulation and C are fp32.
  * Degenerate sizes: M, N or batch == 0 -> success, nothing launched; K == 0 -> C = beta*C.
  * Errors: KS_ERR_INVALID_ARG (see ks_status), KS_ERR_UNSUPPORTED when M, N or K >= 2^31 - 512,

@@ -276,8 +276,25 @@ extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M,
     transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batch, strideA, strideB, strideC, \
         static_cast<hipStream_t>(stream)
 
+// Kernel for the selecting entry points: the tree's choice, unless that is a split-K instance and
+// the registered workspace cannot hold its partial sums; then the instance with the same tiles
+// and no split is used instead, so that a caller who never registers a workspace is still served.
 static int select_checked(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int tA, int tB) {
-    return ks_select(dtype, M, N, K, batch, tA, tB);
+    const int id = ks_select(dtype, M, N, K, batch, tA, tB);
+    if (id < 0) return id;
+    const InstanceDesc *d = desc_of(dtype, id);
+    if (!d || d->splitK <= 1 || M <= 0 || N <= 0 || batch <= 0) return id;
+    const size_t need = (size_t)d->splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+    if (g_ws && g_wsBytes >= need) return id;
+    const int n = dtype == KS_F32 ? kNumF32 : kNumBf16;
+    for (int pass = 0; pass < 2; ++pass)          // same K-step first, then any K-step
+        for (int i = 0; i < n; ++i) {
+            const InstanceDesc *e = desc_of(dtype, i);
+            if (e->splitK == 1 && e->core == d->core && e->bm == d->bm && e->bn == d->bn &&
+                e->p1 == d->p1 && e->p2 == d->p2 && (pass == 1 || e->bk == d->bk))
+                return i;
+        }
+    return id;
 }
 
 extern "C" int ks_gemm_f32_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N,
@@ -322,7 +339,7 @@ extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, in
     if (dtype != KS_F32 && dtype != KS_BF16) return KS_ERR_INVALID_ARG;
     if (iters < 1 || iters > 1024 || reps < 1 || warmup < 0 || !ms_out) return KS_ERR_INVALID_ARG;
     if (kernel_id < 0) {
-        kernel_id = ks_select(dtype, M, N, K, batch, transA, transB);
+        kernel_id = select_checked(dtype, M, N, K, batch, transA, transB);
         if (kernel_id < 0) return kernel_id;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);

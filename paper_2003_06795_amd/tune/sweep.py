@@ -100,6 +100,8 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--min-sample-us", type=float, default=100.0)
     ap.add_argument("--max-cell-ms", type=float, default=400.0)
+    ap.add_argument("--max-workspace-gib", type=float, default=2.0,
+                    help="split-K cells needing more scratch than this are recorded as unusable")
     ap.add_argument("--max-elems", type=float, default=6e9, help="skip workloads with more operand elements")
     a = ap.parse_args(argv)
 
@@ -130,7 +132,14 @@ def main(argv=None):
         buf = Buffers(dtype, M, N, K, batch, seed=1000 * a.config + ri)
         for kid in kids:
             need = ks.workspace_bytes_needed(dt, kid, M, N, batch)
+            if need > a.max_workspace_gib * 2 ** 30:
+                # the split-K form is not usable here: recorded as (practically) infinitely slow
+                wr.writerow(dict(config=a.config, row=ri, dtype=dtype, transA=tA, transB=tB, M=M, N=N, K=K,
+                                 batch=batch, kernel=kid, median_ms="1e9", min_ms="1e9", iters=0, reps=0))
+                continue
             if need and (ws is None or ws.numel() * 4 < need):
+                ks.set_workspace(None)
+                ws = None
                 ws = torch.empty(need // 4 + 1, dtype=torch.float32, device="cuda")
                 ks.set_workspace(ws)
             med, mn, n, reps = time_cell(dtype, kid, tA, tB, M, N, K, batch, alpha, beta, buf,
