@@ -24,9 +24,12 @@ sys.path.insert(0, ROOT)
 PEAK = {"f32": 157.3, "bf16": 2516.6}      # dense matrix-core TFLOP/s of MI355X
 HBM_PEAK_GBS = 8000.0
 CALIB_BYTES = 256 * 1024 * 1024
+SAMPLES = 3                                 # timed samples per row per step
 
 
-def kernel_symbol(ks, dt, kid, tA, tB, vec=True):
+def kernel_symbol(ks, dt, kid, tA, tB, vec=True, dma=False):
+    """Name of the device function a call resolves to (as rocprofv3 prints it).  dma: the bf16
+    direct-to-LDS path applies (aligned operands and K a multiple of the K-step)."""
     ki = ks.kernel_info(dt, kid)
     akc, bkc = int(not tA), int(bool(tB))
     b = lambda v: "true" if v else "false"
@@ -35,6 +38,10 @@ def kernel_symbol(ks, dt, kid, tA, tB, vec=True):
         return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s>" % (
             ki["core"], ki["bm"], ki["bn"], ki["bk"], p1, p2, b(akc), b(bkc), b(vec))
     f = 16 if ki["core_name"] == "mfma16" else 32
+    if vec and dma:
+        stages = ki["lds_bytes"] // (ki["bk"] * (ki["bm"] + ki["bn"]) * 2)
+        return "gemm_bf16_dma_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s>" % (
+            f, ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], stages, b(akc), b(bkc))
     return "gemm_bf16_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s>" % (
         f, ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], b(akc), b(bkc), b(vec))
 
@@ -77,18 +84,20 @@ def allocate(rows, torch):
 
 
 def run_pass(ks, rows, bufs, reps, stream, out_ms=None):
-    """One pass: every row's GEMM with the selected kernel (kernel id -1 = ks_select), launched
-    reps[i] times back to back inside the library between one HIP event pair (ks_time_gemm, the
-    tuner's own clock).  out_ms[i] receives the per-launch milliseconds."""
+    """One pass: every row's GEMM with the selected kernel (kernel id -1 = ks_select), timed the way
+    the tuner times a cell (ks_time_gemm): one untimed launch, then SAMPLES samples of reps[i]
+    back-to-back launches, each between one HIP event pair.  The untimed launch keeps the queue
+    ahead of the device, so a sample measures kernel time and not the host's enqueue rate.
+    out_ms[i] receives the median per-launch milliseconds of the samples."""
     for i, r in enumerate(rows):
         A, B, C = bufs[(r["dtype"], r["shape"])]
         M, N, K, b = r["M"], r["N"], r["K"], r["batch"]
         ms = ks.time_gemm(ks.F32 if r["dtype"] == "f32" else ks.BF16, -1, r["tA"], r["tB"], M, N, K,
                           r["alpha"], A, M if r["tA"] else K, B, K if r["tB"] else N, r["beta"], C, N, b,
                           M * K if b > 1 else 0, K * N if b > 1 else 0, M * N if b > 1 else 0,
-                          stream=stream, warmup=0, iters=1, reps=reps[i])
+                          stream=stream, warmup=1, iters=SAMPLES, reps=reps[i])
         if out_ms is not None:
-            out_ms[i] = ms[0]
+            out_ms[i] = float(np.median(ms))
 
 
 def stored_traffic(workload, symbol):
@@ -104,7 +113,7 @@ def stored_traffic(workload, symbol):
     return None
 
 
-def cpu_baseline(rows, budget_s=15.0):
+def cpu_baseline(rows, budget_s=12.0):
     """The CPU oracle, as it stands, on a seeded sample of the same rows (small ones first so the
     sample is bounded); reports the geometric mean of its TFLOP/s over the sampled rows."""
     import workloads as wl
@@ -114,7 +123,7 @@ def cpu_baseline(rows, budget_s=15.0):
     for i in order:
         r = rows[int(i)]
         macs = r["M"] * r["N"] * r["K"] * r["batch"]
-        if macs > 2 ** 31 or spent > budget_s:
+        if macs > 2 ** 34 or spent > budget_s:
             continue
         p = wl.make_problem(r["dtype"], r["tA"], r["tB"], r["M"], r["N"], r["K"], batch=r["batch"],
                             alpha=r["alpha"], beta=r["beta"], seed=1, key=int(i),
@@ -127,18 +136,18 @@ def cpu_baseline(rows, budget_s=15.0):
         spent += dt
         picked.append(int(i))
         rates.append(2.0 * macs / dt / 1e12)
-        if len(picked) >= 40:
+        if len(picked) >= 400:
             break
     return dict(value=float(np.exp(np.mean(np.log(rates)))), unit="TFLOP/s (geomean over sampled rows)",
                 cores=og.num_threads(), kind="oracle",
-                sample="%d seeded rows of the workload with M*N*K <= 2^31, full fp64 triple loop, %.1f s of CPU work"
+                sample="%d seeded rows of the workload with M*N*K <= 2^34, full fp64 triple loop, %.1f s of CPU work"
                        % (len(picked), spent))
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
@@ -172,9 +181,10 @@ def main():
 
     # Like the tuner, a row's sample is a short run of back-to-back launches (issued natively by
     # ks_time_gemm) so that the event interval measures kernel time rather than host dispatch.  The
-    # repetition count is a fixed function of the row's flops (about 3e8 flops per sample, at
-    # most 16 launches), so warm-up and timed passes launch exactly the same kernels.
-    reps = [int(min(16, max(1, np.ceil(3e8 / (2.0 * r["M"] * r["N"] * r["K"] * r["batch"]))))) for r in rows]
+    # repetition count is a fixed function of the row's flops (about 1.2e9 flops per sample, at
+    # most 64 launches: roughly the tuner's 100 us samples), so warm-up and timed passes launch
+    # exactly the same kernels.
+    reps = [int(min(64, max(1, np.ceil(1.2e9 / (2.0 * r["M"] * r["N"] * r["K"] * r["batch"]))))) for r in rows]
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(a.warmup):
         run_pass(ks, rows, bufs, reps, stream)
@@ -199,12 +209,14 @@ def main():
             for i, r in enumerate(rows):
                 f.write("%d,%d,%d,%d,%d,%d,%d,%d,%.6g,%.6g\n" % (i, r["tA"], r["tB"], r["M"], r["N"], r["K"],
                                                                chosen[i], reps[i], med[i], tflops[i]))
-    sym = [kernel_symbol(ks, dt, k, r["tA"], r["tB"]) for k, r in zip(chosen, rows)]
+    sym = [kernel_symbol(ks, dt, k, r["tA"], r["tB"], vec=all(v % 8 == 0 for v in (r["M"], r["N"], r["K"])),
+                         dma=dtype == "bf16" and r["K"] % ks.kernel_info(dt, k)["bk"] == 0)
+           for k, r in zip(chosen, rows)]
     by = {}
     for i, s in enumerate(sym):
         d = by.setdefault(s, dict(time=0.0, flops=0.0, bytes=0.0, launches=0))
-        n = a.steps * reps[i]
-        d["time"] += float(ms[:, i].sum()) * 1e-3 * reps[i]
+        n = a.steps * SAMPLES * reps[i]
+        d["time"] += float(ms[:, i].sum()) * 1e-3 * SAMPLES * reps[i]
         d["flops"] += float(flops[i]) * n
         r = rows[i]
         esz = 4 if dtype == "f32" else 2
@@ -213,10 +225,13 @@ def main():
     dom = max(by, key=lambda s: by[s]["time"])
     d = by[dom]
     achieved = d["flops"] / d["time"] / 1e12
+    traffic = stored_traffic(a.workload, dom)
+    if traffic is not None:
+        traffic["algorithmic_bytes"] = d["bytes"] / d["launches"]
     roofline = dict(bound="mfma", kernel=dom, achieved=achieved, peak=PEAK[dtype], unit="TFLOP/s",
-                    frac=achieved / PEAK[dtype], traffic=stored_traffic(a.workload, dom), launches_per_step=d["launches"] // a.steps,
+                    frac=achieved / PEAK[dtype], traffic=traffic, launches_per_step=d["launches"] // a.steps,
                     avg_launch_us=d["time"] / d["launches"] * 1e6,
-                    share_of_step_time=d["time"] / float((ms * np.array(reps)[None, :]).sum() * 1e-3),
+                    share_of_step_time=d["time"] / float((ms * np.array(reps)[None, :]).sum() * 1e-3 * SAMPLES),
                     algorithmic_gbs=d["bytes"] / d["time"] / 1e9)
 
     out = {
@@ -228,9 +243,10 @@ def main():
                                 "selected kernel per row" if a.workload == "cfg2" else
                                 "bf16 large/skinny set: 7 shapes x {NN,NT}, selected kernel per row"),
                    "rows": len(rows), "kernels_used": len(set(chosen)),
-                   "launches_per_step": int(sum(reps)),
-                   "timing": "per row: median over steps of (HIP-event interval around reps back-to-back launches inside ks_time_gemm) / reps"},
-        "device_ms_per_step": float((ms * np.array(reps)[None, :]).sum() / a.steps),
+                   "launches_per_step": int(sum(1 + SAMPLES * r for r in reps)),
+                   "timing": ("per row and step: ks_time_gemm with 1 untimed launch and %d samples of `reps` back-to-back "
+                              "launches between HIP events; row time = median over steps of the per-step median" % SAMPLES)},
+        "timed_device_ms_per_step": float((ms * np.array(reps)[None, :]).sum() * SAMPLES / a.steps),
         "best_row_tflops": float(tflops.max()),
         "roofline": roofline,
     }
@@ -239,9 +255,15 @@ def main():
     if os.path.exists(rep):
         R = json.load(open(rep))
         dep = [s for s in R["sweep"] if s["n_kept"] == R["deployed"]["n_kept"]][0]
-        out["selector"] = dict(source="stored exhaustive sweep, held-out 30% of shapes", n_kept=dep["n_kept"],
-                               kept=dep["kept"], selected_over_best_geomean=dep["test"]["selector"],
-                               achievable_geomean=dep["test"]["achievable"])
+        key = "2" if a.workload == "cfg2" else "6"
+        held = dep.get("test_by_config", {}).get(key, dep["test"])
+        out["selector"] = dict(source="stored exhaustive sweeps (%s), held-out 30%% of this workload's shapes"
+                                      % ", ".join(os.path.basename(t) for t in R["timings"]),
+                               leaf_limit=dep["n_kept"], kept=dep["kept"],
+                               selected_over_best_geomean=held["selector"],
+                               achievable_geomean=held["achievable"],
+                               best_single_kernel_geomean=held["best_single"],
+                               held_out_by_config={c: v["selector"] for c, v in dep.get("test_by_config", {}).items()})
     if not a.no_extra and a.workload == "cfg2":
         out["bf16_large"] = bf16_report(ks, torch)
     if not a.no_cpu:
@@ -263,7 +285,7 @@ def bf16_report(ks, torch):
         if ks.workspace_bytes_needed(ks.BF16, kid, M, N, 1) > ws.numel() * 4:
             continue
         t = ks.time_gemm(ks.BF16, kid, r["tA"], r["tB"], M, N, K, 1.0, A, M if r["tA"] else K, B,
-                         K if r["tB"] else N, 0.0, C, N, warmup=2, iters=5, reps=1)
+                         K if r["tB"] else N, 0.0, C, N, warmup=3, iters=10, reps=1)
         tf = 2.0 * M * N * K / (float(np.median(t)) * 1e-3) / 1e12
         gbs = ((M * K + K * N) * 2 + M * N * 4) / (float(np.median(t)) * 1e-3) / 1e9
         cells.append(dict(M=M, N=N, K=K, layout="N" + "NT"[r["tB"]], kernel=kid, tflops=tf,

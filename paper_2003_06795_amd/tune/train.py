@@ -52,18 +52,28 @@ def perf_of(rows, T):
 
 
 def split_rows(rows):
-    """Train/test masks by SHAPE.  Config 2 (fp32 tuning set, 4 layouts per shape) and config 6
-    (bf16 tuning set, 2 layouts per shape) are split 70/30 with their seeded permutation; rows of
-    any other configuration in the table (e.g. the named bf16 large/skinny cells) are training
-    rows only."""
+    """Train/test masks by SHAPE, 70/30, seeded.  Config 2 (fp32 tuning set, 4 layouts per shape)
+    and config 6 (bf16 tuning set, 2 layouts per shape) use the permutations defined with the
+    workloads; configs 3 and 4 (one row per shape) are split by a permutation of the shapes present
+    in the table seeded with the config number; the named bf16 large/skinny cells (config 5) are
+    training rows only."""
     tr = np.zeros(len(rows), dtype=bool)
     te = np.zeros(len(rows), dtype=bool)
     s2, s6 = wl.config2_split(), wl.bf16_tuning_split()
+    other = {}
+    for cfg in (3, 4):
+        ids = sorted({r["row"] for r in rows if r["config"] == cfg})
+        perm = np.random.default_rng([cfg, 0x5917]).permutation(len(ids))
+        n_train = int(round(0.7 * len(ids)))
+        other[cfg] = {ids[int(j)] for j in perm[:n_train]}
     for i, r in enumerate(rows):
         if r["config"] == 2:
             tr[i], te[i] = r["row"] // 4 in s2[0], r["row"] // 4 in s2[1]
         elif r["config"] == 6:
             tr[i], te[i] = r["row"] // 2 in s6[0], r["row"] // 2 in s6[1]
+        elif r["config"] in other:
+            tr[i] = r["row"] in other[r["config"]]
+            te[i] = not tr[i]
         else:
             tr[i] = True
     return tr, te
@@ -123,7 +133,7 @@ def tree_from_json(rows):
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--timings", required=True)
+    ap.add_argument("--timings", required=True, nargs="+", help="one or more timing tables (rows are pooled)")
     ap.add_argument("--n-kept", type=int, default=8)
     ap.add_argument("--max-depth", type=int, default=12)
     ap.add_argument("--min-samples-leaf", type=int, default=1)
@@ -135,14 +145,19 @@ def main(argv=None):
     ap.add_argument("--report", default=None)
     a = ap.parse_args(argv)
 
-    rows, T = load_table(a.timings, a.dtype)
+    rows, T = [], []
+    for path in a.timings:
+        r_, t_ = load_table(path, a.dtype)
+        rows += r_
+        T.append(t_)
+    T = np.concatenate(T, axis=0)
     P = perf_of(rows, T)
     X = features_of(rows, a.features)
     if a.all_rows:
         tr = te = np.ones(len(rows), dtype=bool)
     else:
         tr, te = split_rows(rows)
-    report = dict(dtype=a.dtype, timings=os.path.relpath(a.timings), rows=len(rows),
+    report = dict(dtype=a.dtype, timings=[os.path.relpath(t) for t in a.timings], rows=len(rows),
                   train_rows=int(tr.sum()), test_rows=int(te.sum()), features=a.features,
                   max_depth=a.max_depth, min_samples_leaf=a.min_samples_leaf, weighted=a.weighted,
                   sweep=[])
@@ -150,11 +165,20 @@ def main(argv=None):
     for n in sorted({4, 5, 6, 8, 15, a.n_kept}):
         kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted)
         ev_tr, ev_te = evaluate(tree, kept, X[tr], P[tr]), evaluate(tree, kept, X[te], P[te])
-        report["sweep"].append(dict(n_kept=n, kept=kept.tolist(), tree_nodes=len(tree), train=ev_tr, test=ev_te))
+        per_cfg = {}
+        for cfg in sorted({r["config"] for r in rows}):
+            m = te & np.array([r["config"] == cfg for r in rows])
+            if m.any():
+                per_cfg[str(cfg)] = evaluate(tree, kept, X[m], P[m])
+        report["sweep"].append(dict(n_kept=n, kept=kept.tolist(), tree_nodes=len(tree), train=ev_tr, test=ev_te,
+                                    test_by_config=per_cfg))
         print("N=%2d kept=%-40s nodes=%3d | train achievable %.4f selector %.4f | test achievable %.4f "
               "selector %.4f (best single %.4f)" % (n, kept.tolist(), len(tree), ev_tr["achievable"],
                                                     ev_tr["selector"], ev_te["achievable"],
                                                     ev_te["selector"], ev_te["best_single"]))
+        if len(per_cfg) > 1:
+            print("      held-out by config: " + "  ".join("cfg%s: achievable %.4f selector %.4f" % (
+                c, v["achievable"], v["selector"]) for c, v in per_cfg.items()))
         if n == a.n_kept:
             chosen_fit = (kept, reg, tree)
     kept, reg, tree = chosen_fit
