@@ -119,7 +119,7 @@ struct Bf16TileLoader {
     }
 };
 
-template <int F, int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool VEC>
+template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT, bool AKC, bool BKC, bool VEC>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_kernel(const GemmParams p) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     constexpr int FM = WM / F, FN = WN / F;
@@ -202,9 +202,9 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_kernel(c
     (void)LGRP;
 
     if constexpr (F == 16)
-        write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
+        write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
     else
-        write_tile_mfma32<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
+        write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
 }
 
 }  // namespace ks

@@ -109,7 +109,7 @@ struct InterleaveHint {
     }
 };
 
-template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool AKC, bool BKC>
+template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT, bool AKC, bool BKC>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kernel(const GemmParams p) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int FM = WM / F, FN = WN / F;
@@ -276,9 +276,9 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
     if constexpr (STAGES > 2) { if (t + 2 < nk) step(t + 2, std::integral_constant<int, 2>{}); }
 
     if constexpr (F == 16)
-        write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
+        write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
     else
-        write_tile_mfma32<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
+        write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
 }
 
 }  // namespace ks

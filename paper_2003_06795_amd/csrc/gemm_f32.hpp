@@ -9,6 +9,7 @@
 //               MFMA16  each wave owns WM x WN built from 16x16x4 fp32 MFMA fragments
 //               MFMA32  each wave owns WM x WN built from 32x32x2 fp32 MFMA fragments
 //   P1 x P2   TM x TN for FMA, WM x WN for the MFMA cores
+//   SPLIT     the instantiation is a split-K member: partial sums go to the workspace
 //   AKC/BKC   whether op(A)/op(B) is K-contiguous in memory (A: transA == 0, B: transB == 1);
 //             decides the coalescing direction of the global loads
 //   VEC       operands are 16-byte aligned with leading dimensions and contiguous extents that
@@ -100,7 +101,7 @@ struct TileLoader {
     }
 };
 
-template <int CORE, int BM, int BN, int BK, int P1, int P2, bool AKC, bool BKC, bool VEC>
+template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, bool AKC, bool BKC, bool VEC>
 __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gemm_f32_kernel(
     const GemmParams p) {
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
@@ -230,16 +231,16 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
 
     // epilogue
     if constexpr (CORE == CORE_FMA) {
-        write_tile(p, tc, Cb, [&](auto emit) {
+        write_tile<SPLIT>(p, tc, Cb, [&](auto emit) {
 #pragma unroll
             for (int i = 0; i < P1; ++i)
 #pragma unroll
                 for (int j = 0; j < P2; ++j) emit(row0 + subM + i, col0 + subN + j, accF[i][j]);
         });
     } else if constexpr (CORE == CORE_MFMA16) {
-        write_tile_mfma16<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
+        write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
     } else {
-        write_tile_mfma32<FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
+        write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
     }
 }
 

@@ -10,11 +10,11 @@
 
 namespace ks {
 
-template <int F, int BM, int BN, int BK, int WM, int WN>
+template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT>
 static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     const dim3 g((unsigned)grid), b(NT);
-#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, A, B, V>), g, b, 0, s, p)
+#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, SPLIT, A, B, V>), g, b, 0, s, p)
     switch (variant) {
         case 0: KS_V(false, false, false); break;
         case 1: KS_V(false, false, true); break;
@@ -31,7 +31,7 @@ static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t 
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16<F, BM, BN, BK, WM, WN>;
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16<F, BM, BN, BK, WM, WN, ((SPLITK) > 1)>;
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 }

@@ -11,11 +11,11 @@
 namespace ks {
 
 // variant = akc * 2 + bkc
-template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES>
+template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT>
 static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     const dim3 g((unsigned)grid), b(NT);
-#define KS_V(A, B) hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, A, B>), g, b, 0, s, p)
+#define KS_V(A, B) hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B>), g, b, 0, s, p)
     switch (variant) {
         case 0: KS_V(false, false); break;
         case 1: KS_V(false, true); break;
@@ -28,7 +28,7 @@ static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStrea
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16_dma<F, BM, BN, BK, WM, WN, STAGES>;
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16_dma<F, BM, BN, BK, WM, WN, STAGES, ((SPLITK) > 1)>;
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 }

@@ -11,11 +11,11 @@
 
 namespace ks {
 
-template <int CORE, int BM, int BN, int BK, int P1, int P2>
+template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT>
 static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads;
     const dim3 g((unsigned)grid), b(NT);
-#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, A, B, V>), g, b, 0, s, p)
+#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p)
     switch (variant) {
         case 0: KS_V(false, false, false); break;
         case 1: KS_V(false, false, true); break;
@@ -32,7 +32,7 @@ static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2>;
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) > 1)>;
 #include "instances.def"
 #undef KS_F32_INSTANCE
 }

@@ -51,14 +51,14 @@ __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
 // Epilogue.  `visit(f)` calls f(row, col, acc) for every accumulator element this lane owns
 // (tile-relative to the matrix, i.e. absolute row / col).  The three output modes are separated
 // outside the element loops so the per-element code is a bounds test and one store:
-//   split-K: raw partial sum to this split's slice of the workspace;
+//   SPLIT (a split-K instantiation): raw partial sum to this split's slice of the workspace;
 //   beta == 0: C = alpha * acc (C is never read);
 //   otherwise: C = alpha * acc + beta * C.
-template <class Visit>
+template <bool SPLIT, class Visit>
 __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord &tc, float *Cb,
                                            Visit visit) {
     const int M = p.M, N = p.N;
-    if (p.splitK > 1) {
+    if constexpr (SPLIT) {
         float *w = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)M * N;
         visit([&](int row, int col, float acc) {
             if (row < M && col < N) w[(long long)row * N + col] = acc;
@@ -82,10 +82,10 @@ __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord 
 }
 
 // accumulator register e of lane l of a 16x16 MFMA fragment holds C[4*(l/16) + e][l%16]
-template <int FM, int FN, class Acc>
+template <bool SPLIT, int FM, int FN, class Acc>
 __device__ __forceinline__ void write_tile_mfma16(const GemmParams &p, const TileCoord &tc, float *Cb,
                                                   int rowBase, int colBase, int lane, const Acc &acc) {
-    write_tile(p, tc, Cb, [&](auto emit) {
+    write_tile<SPLIT>(p, tc, Cb, [&](auto emit) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -97,10 +97,10 @@ __device__ __forceinline__ void write_tile_mfma16(const GemmParams &p, const Til
 }
 
 // accumulator register e of lane l of a 32x32 MFMA fragment holds C[8*(e/4) + 4*(l/32) + e%4][l%32]
-template <int FM, int FN, class Acc>
+template <bool SPLIT, int FM, int FN, class Acc>
 __device__ __forceinline__ void write_tile_mfma32(const GemmParams &p, const TileCoord &tc, float *Cb,
                                                   int rowBase, int colBase, int lane, const Acc &acc) {
-    write_tile(p, tc, Cb, [&](auto emit) {
+    write_tile<SPLIT>(p, tc, Cb, [&](auto emit) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
