@@ -94,6 +94,31 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// LDS -> registers: the MFMA operand of one fragment, i.e. for lane l the eight consecutive k
+// starting at kk + 8*(l / F) of tile row rowBase + l % F.  KC tiles ([row][BK], swizzled chunks)
+// need one ds_read_b128; row-contiguous tiles ([k][ROWS]) two transposing ds_read_b64_tr_b16, in
+// which lane s of a 16-lane group addresses rows 4*(s%4).. of k row s/4 and lane l receives the
+// four k values of row l.
+template <int F, int ROWS, int BK, bool KC>
+__device__ __forceinline__ bf16x8 read_fragment(const char *tile, int rowBase, int kk, int lane) {
+    const int lgrp = lane / F;
+    if constexpr (KC) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
+            tile + 16 * Bf16Lds<BK>::chunk(rowBase + lane % F, kk / 8 + lgrp)));
+    } else {
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        using LT = Bf16LdsT<ROWS>;
+        const int trRow = 4 * (lane & 3) + (F == 32 ? 16 * ((lane >> 4) & 1) : 0);
+        const int kb = kk + 8 * lgrp + ((lane & 15) >> 2);
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(tile + LT::byte_of(kb, rowBase + trRow)));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(tile + LT::byte_of(kb + 4, rowBase + trRow)));
+        const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    }
+}
+
 // Scheduling hint for one k-substep: NM MFMAs with NR LDS reads spread evenly between them.
 template <int M, int NM, int NR>
 struct InterleaveHint {
@@ -116,7 +141,6 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
     constexpr int KSTEP = F == 32 ? 16 : 32;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     static_assert(STAGES >= 2 && STAGES <= 4, "stages");
-    using LK = Bf16Lds<BK>;
     // one __shared__ object per stage: the compiler can then tell that the stage being filled by
     // the in-flight loads is not the stage the ds_reads touch, and does not serialise them
     __shared__ __attribute__((aligned(1024))) char As0[A_BYTES];
@@ -151,10 +175,6 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
     pb.init(wave, lane, p.ldb, col0, p.N);
 
     const int subM = (wave / (BN / WN)) * WM, subN = (wave % (BN / WN)) * WN;
-    const int lrow = lane % F, lgrp = lane / F;
-    // transposing read: lane s of a 16-lane group addresses rows 4*(s%4).. of k row s/4 (+ group base)
-    const int trRow = 4 * (lane & 3) + (F == 32 ? 16 * ((lane >> 4) & 1) : 0);
-    const int trK = (lane & 15) >> 2;
 
     floatx4 acc16[F == 16 ? FM : 1][F == 16 ? FN : 1];
     floatx16 acc32[F == 32 ? FM : 1][F == 32 ? FN : 1];
@@ -170,39 +190,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
 
     // LDS -> register fragments of one k-substep (KSTEP values of k) for this wave's tile
     auto load_frags = [&](const char *as, const char *bs, int kk, bf16x8 (&a)[FM], bf16x8 (&b)[FN]) {
-        typedef short shortx8 __attribute__((ext_vector_type(8)));
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            if constexpr (AKC) {
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
-                    as + 16 * LK::chunk(subM + i * F + lrow, kk / 8 + lgrp)));
-            } else {
-                using LT = Bf16LdsT<BM>;
-                const int kb = kk + 8 * lgrp + trK;
-                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb, subM + i * F + trRow)));
-                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(as + LT::byte_of(kb + 4, subM + i * F + trRow)));
-                const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                a[i] = __builtin_bit_cast(bf16x8, v);
-            }
-        }
+        for (int i = 0; i < FM; ++i) a[i] = read_fragment<F, BM, BK, AKC>(as, subM + i * F, kk, lane);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            if constexpr (BKC) {
-                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4 *>(
-                    bs + 16 * LK::chunk(subN + j * F + lrow, kk / 8 + lgrp)));
-            } else {
-                using LT = Bf16LdsT<BN>;
-                const int kb = kk + 8 * lgrp + trK;
-                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb, subN + j * F + trRow)));
-                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)(lds_void_ptr)(bs + LT::byte_of(kb + 4, subN + j * F + trRow)));
-                const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                b[j] = __builtin_bit_cast(bf16x8, v);
-            }
-        }
+        for (int j = 0; j < FN; ++j) b[j] = read_fragment<F, BN, BK, BKC>(bs, subN + j * F, kk, lane);
     };
 
     // One K-step on a landed stage.  The fragments of k-substep s+1 are fetched while the MFMAs of
