@@ -236,3 +236,94 @@ def prune_and_train(X_train, P_train, n_kept, max_depth=12, min_samples_leaf=1):
     y = labels_within(P_train, kept)
     clf = fit_classification_tree(X_train, y, max_depth, min_samples_leaf)
     return dict(regression_tree=reg, kept=kept, labels=y, selector=clf)
+
+
+# ----------------------------------------------------------------- the other pruning methods
+# Section III compares the decision tree with: the N configurations that win most often, k-means
+# on the normalised performance vectors, k-means in PCA coordinates with the centroids mapped back,
+# and HDBSCAN (not implemented here).  Section II-B uses the PCA variance spectrum of the same
+# vectors to choose the range of N.  Readings, where the paper gives no detail:
+#   * k-means is Lloyd's algorithm with a deterministic "maximin" seeding instead of a random one:
+#     the first centre is the row closest to the mean of all rows, every further centre is the row
+#     farthest (squared Euclidean distance) from its nearest centre so far; lowest row on ties.
+#     A row goes to its nearest centre (lowest centre index on ties); a centre that loses all its
+#     rows stays where it is; iteration stops when no row changes cluster (or after max_iter).
+#   * the representative of a cluster is its centroid and the kept configuration its argmax;
+#   * PCA is the eigen-decomposition of the covariance of the centred rows; the number of
+#     components used for clustering is a parameter (compare.py takes the smallest number that
+#     explains 95 % of the variance).
+
+def prune_top_n(Phat, n):
+    """The n configurations that are optimal (normalised performance 1, first on ties) most often;
+    equal counts resolve to the lowest id; configurations that never win are not kept."""
+    Phat = np.asarray(Phat, dtype=np.float64)
+    wins = np.bincount(np.argmax(Phat, axis=1), minlength=Phat.shape[1])
+    order = sorted(range(Phat.shape[1]), key=lambda c: (-wins[c], c))
+    return sorted(c for c in order[:n] if wins[c] > 0)
+
+
+def _maximin_seeds(Z, k):
+    mean = Z.mean(axis=0)
+    first = int(np.argmin(((Z - mean) ** 2).sum(axis=1)))
+    seeds = [first]
+    d = ((Z - Z[first]) ** 2).sum(axis=1)
+    while len(seeds) < k:
+        nxt = int(np.argmax(d))
+        seeds.append(nxt)
+        d = np.minimum(d, ((Z - Z[nxt]) ** 2).sum(axis=1))
+    return seeds
+
+
+def kmeans(Z, k, max_iter=100):
+    """Lloyd's algorithm with maximin seeding.  Returns (centres [k x d], assignment [rows])."""
+    Z = np.asarray(Z, dtype=np.float64)
+    k = min(k, Z.shape[0])
+    centres = Z[_maximin_seeds(Z, k)].copy()
+    assign = np.full(Z.shape[0], -1)
+    for _ in range(max_iter):
+        d = ((Z[:, None, :] - centres[None, :, :]) ** 2).sum(axis=2)
+        new = np.argmin(d, axis=1)
+        if np.array_equal(new, assign):
+            break
+        assign = new
+        for c in range(k):
+            if np.any(assign == c):
+                centres[c] = Z[assign == c].mean(axis=0)
+    return centres, assign
+
+
+def prune_kmeans(Phat, n, max_iter=100):
+    centres, _ = kmeans(Phat, n, max_iter)
+    return sorted({int(np.argmax(c)) for c in centres})
+
+
+def pca(Phat):
+    """(mean, eigenvalues descending, eigenvectors as columns) of the covariance of the rows."""
+    X = np.asarray(Phat, dtype=np.float64)
+    mean = X.mean(axis=0)
+    cov = (X - mean).T @ (X - mean) / max(X.shape[0] - 1, 1)
+    w, V = np.linalg.eigh(cov)
+    order = np.argsort(-w, kind="stable")
+    return mean, np.maximum(w[order], 0.0), V[:, order]
+
+
+def pca_variance_ratio(Phat):
+    """Fraction of the total variance carried by each principal component, descending."""
+    _, w, _ = pca(Phat)
+    return w / w.sum()
+
+
+def components_for(ratio, fraction):
+    """Smallest number of leading components whose variance fractions add up to `fraction`."""
+    return int(np.searchsorted(np.cumsum(ratio), fraction - 1e-12) + 1)
+
+
+def prune_pca_kmeans(Phat, n, dims, max_iter=100):
+    """k-means in the coordinates of the leading `dims` principal components; each centroid is
+    mapped back to configuration space (mean + coordinates . components) and its argmax kept."""
+    X = np.asarray(Phat, dtype=np.float64)
+    mean, _, V = pca(X)
+    Vd = V[:, :dims]
+    centres, _ = kmeans((X - mean) @ Vd, n, max_iter)
+    back = mean + centres @ Vd.T
+    return sorted({int(np.argmax(c)) for c in back})
