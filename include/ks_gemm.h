@@ -187,6 +187,25 @@ int ks_tune_prune_tree(const int64_t *features, int n_features, const double *no
                        int rows, int cols, int max_leaves, int min_samples_leaf,
                        int32_t *kept_out, ks_tree_node_t *tree_out, int *tree_nodes_out);
 
+/* Section III, the methods the decision tree is compared with.  Each writes the sorted distinct
+ * kept ids to kept_out (capacity n) and returns how many, or a negative status.
+ *   top_n:   the n configurations that are optimal for the most rows (equal counts -> lowest id;
+ *            configurations that never win are not kept).
+ *   kmeans:  Lloyd's k-means with n clusters on the rows of `normalised`, deterministic maximin
+ *            seeding (first centre: row nearest to the mean; next: row farthest from its nearest
+ *            centre; lowest row on ties), stop when no row changes cluster or after max_iter.
+ *            pca_dims == 0: cluster in configuration space and keep each centroid's best
+ *            configuration.  pca_dims > 0: cluster in the coordinates of that many leading
+ *            principal components (covariance of the centred rows), map each centroid back
+ *            (mean + coordinates . components) and keep its best configuration. */
+int ks_tune_prune_top_n(const double *normalised, int rows, int cols, int n, int32_t *kept_out);
+int ks_tune_prune_kmeans(const double *normalised, int rows, int cols, int n, int pca_dims,
+                         int max_iter, int32_t *kept_out);
+
+/* Section II-B: fraction of the total variance of the rows of `normalised` carried by each
+ * principal component, descending (ratio_out: cols doubles). */
+int ks_tune_pca_variance(const double *normalised, int rows, int cols, double *ratio_out);
+
 /* Section III-A score: geometric mean over rows of max_{c in kept} normalised[s][c]. */
 int ks_tune_achievable(const double *normalised, int rows, int cols, const int32_t *kept,
                        int n_kept, double *score_out);

@@ -56,7 +56,8 @@ EXPORTS = [
     "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
-    "ks_tune_predict", "ks_tune_selector_score", "ks_status_string",
+    "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
+    "ks_tune_pca_variance", "ks_status_string",
 ]
 
 
@@ -90,6 +91,9 @@ def lib():
     L.ks_tune_fit_selector.argtypes = [_p, _i, _p, _i, _i, _p, _i, _i, _i, _p, _p, _i]
     L.ks_tune_predict.argtypes = [_p, _i, _p, _i, _i, _p]
     L.ks_tune_selector_score.argtypes = [_p, _i, _i, _p, _p]
+    L.ks_tune_prune_top_n.argtypes = [_p, _i, _i, _i, _p]
+    L.ks_tune_prune_kmeans.argtypes = [_p, _i, _i, _i, _i, _i, _p]
+    L.ks_tune_pca_variance.argtypes = [_p, _i, _i, _p]
     L.ks_status_string.argtypes = [_i]
     L.ks_status_string.restype = ctypes.c_char_p
     _lib = L
@@ -304,3 +308,29 @@ def tune_selector_score(normalised, chosen):
     _check(lib().ks_tune_selector_score(yp, Y.shape[0], Y.shape[1], cp, ctypes.byref(out)),
            "ks_tune_selector_score")
     return out.value
+
+
+def tune_prune_top_n(normalised, n):
+    Y, yp = _np(normalised, np.float64)
+    kept = np.zeros(n, dtype=np.int32)
+    m = lib().ks_tune_prune_top_n(yp, Y.shape[0], Y.shape[1], int(n), kept.ctypes.data_as(_p))
+    if m < 0:
+        raise KsError(m, "ks_tune_prune_top_n")
+    return kept[:m].copy()
+
+
+def tune_prune_kmeans(normalised, n, pca_dims=0, max_iter=100):
+    Y, yp = _np(normalised, np.float64)
+    kept = np.zeros(n, dtype=np.int32)
+    m = lib().ks_tune_prune_kmeans(yp, Y.shape[0], Y.shape[1], int(n), int(pca_dims), int(max_iter),
+                                   kept.ctypes.data_as(_p))
+    if m < 0:
+        raise KsError(m, "ks_tune_prune_kmeans")
+    return kept[:m].copy()
+
+
+def tune_pca_variance(normalised):
+    Y, yp = _np(normalised, np.float64)
+    out = np.zeros(Y.shape[1], dtype=np.float64)
+    _check(lib().ks_tune_pca_variance(yp, Y.shape[0], Y.shape[1], out.ctypes.data_as(_p)), "ks_tune_pca_variance")
+    return out

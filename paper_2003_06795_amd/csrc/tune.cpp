@@ -294,3 +294,217 @@ extern "C" int ks_tune_selector_score(const double *normalised, int rows, int co
     *score_out = std::exp(logSum / rows);
     return KS_OK;
 }
+
+// ------------------------------------------------------------------------------------------------
+// The paper's other pruning methods (Section III) and the PCA variance spectrum (Section II-B).
+// k-means is Lloyd's algorithm with deterministic maximin seeding (first centre: the row nearest
+// to the mean of all rows; each further centre: the row farthest from its nearest centre so far;
+// lowest row on ties).  A centre that loses all its rows stays where it is.
+namespace {
+
+double dist2(const double *a, const double *b, int d) {
+    double s = 0.0;
+    for (int j = 0; j < d; ++j) {
+        const double t = a[j] - b[j];
+        s += t * t;
+    }
+    return s;
+}
+
+// Z: rows x d.  centres: k x d (k <= rows).  Returns the assignment of every row.
+std::vector<int> lloyd(const std::vector<double> &Z, int rows, int d, int k, int maxIter,
+                       std::vector<double> &centres) {
+    std::vector<double> mean(d, 0.0);
+    for (int s = 0; s < rows; ++s)
+        for (int j = 0; j < d; ++j) mean[j] += Z[(size_t)s * d + j];
+    for (int j = 0; j < d; ++j) mean[j] /= rows;
+    int first = 0;
+    double best = dist2(&Z[0], mean.data(), d);
+    for (int s = 1; s < rows; ++s) {
+        const double v = dist2(&Z[(size_t)s * d], mean.data(), d);
+        if (v < best) { best = v; first = s; }
+    }
+    std::vector<int> seeds{first};
+    std::vector<double> nearest(rows);
+    for (int s = 0; s < rows; ++s) nearest[s] = dist2(&Z[(size_t)s * d], &Z[(size_t)first * d], d);
+    while ((int)seeds.size() < k) {
+        int far = 0;
+        for (int s = 1; s < rows; ++s) if (nearest[s] > nearest[far]) far = s;
+        seeds.push_back(far);
+        for (int s = 0; s < rows; ++s)
+            nearest[s] = std::min(nearest[s], dist2(&Z[(size_t)s * d], &Z[(size_t)far * d], d));
+    }
+    centres.assign((size_t)k * d, 0.0);
+    for (int c = 0; c < k; ++c)
+        std::copy(&Z[(size_t)seeds[c] * d], &Z[(size_t)seeds[c] * d] + d, &centres[(size_t)c * d]);
+    std::vector<int> assign(rows, -1);
+    std::vector<double> sum((size_t)k * d);
+    std::vector<int> count(k);
+    for (int it = 0; it < maxIter; ++it) {
+        bool changed = false;
+        for (int s = 0; s < rows; ++s) {
+            int arg = 0;
+            double bd = dist2(&Z[(size_t)s * d], &centres[0], d);
+            for (int c = 1; c < k; ++c) {
+                const double v = dist2(&Z[(size_t)s * d], &centres[(size_t)c * d], d);
+                if (v < bd) { bd = v; arg = c; }
+            }
+            if (arg != assign[s]) { assign[s] = arg; changed = true; }
+        }
+        if (!changed) break;
+        std::fill(sum.begin(), sum.end(), 0.0);
+        std::fill(count.begin(), count.end(), 0);
+        for (int s = 0; s < rows; ++s) {
+            ++count[assign[s]];
+            for (int j = 0; j < d; ++j) sum[(size_t)assign[s] * d + j] += Z[(size_t)s * d + j];
+        }
+        for (int c = 0; c < k; ++c)
+            if (count[c] > 0)
+                for (int j = 0; j < d; ++j) centres[(size_t)c * d + j] = sum[(size_t)c * d + j] / count[c];
+    }
+    return assign;
+}
+
+// Eigen-decomposition of the covariance of the rows by cyclic Jacobi rotations.
+// w: eigenvalues descending; V: cols x cols, eigenvector i in column i.
+void covariance_eigen(const double *X, int rows, int cols, std::vector<double> &mean,
+                      std::vector<double> &w, std::vector<double> &V) {
+    mean.assign(cols, 0.0);
+    for (int s = 0; s < rows; ++s)
+        for (int j = 0; j < cols; ++j) mean[j] += X[(size_t)s * cols + j];
+    for (int j = 0; j < cols; ++j) mean[j] /= rows;
+    std::vector<double> A((size_t)cols * cols, 0.0);
+    for (int s = 0; s < rows; ++s)
+        for (int i = 0; i < cols; ++i) {
+            const double xi = X[(size_t)s * cols + i] - mean[i];
+            for (int j = i; j < cols; ++j) A[(size_t)i * cols + j] += xi * (X[(size_t)s * cols + j] - mean[j]);
+        }
+    const double denom = rows > 1 ? rows - 1 : 1;
+    for (int i = 0; i < cols; ++i)
+        for (int j = i; j < cols; ++j) A[(size_t)j * cols + i] = A[(size_t)i * cols + j] /= denom;
+    V.assign((size_t)cols * cols, 0.0);
+    for (int i = 0; i < cols; ++i) V[(size_t)i * cols + i] = 1.0;
+    for (int sweep = 0; sweep < 100; ++sweep) {
+        double off = 0.0, diag = 0.0;
+        for (int i = 0; i < cols; ++i) {
+            diag += A[(size_t)i * cols + i] * A[(size_t)i * cols + i];
+            for (int j = i + 1; j < cols; ++j) off += A[(size_t)i * cols + j] * A[(size_t)i * cols + j];
+        }
+        if (off <= 1e-30 * (diag + off) || off == 0.0) break;
+        for (int p = 0; p < cols; ++p)
+            for (int q = p + 1; q < cols; ++q) {
+                const double apq = A[(size_t)p * cols + q];
+                if (apq == 0.0) continue;
+                const double theta = (A[(size_t)q * cols + q] - A[(size_t)p * cols + p]) / (2.0 * apq);
+                const double t = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
+                const double c = 1.0 / std::sqrt(t * t + 1.0), sn = t * c;
+                for (int k = 0; k < cols; ++k) {
+                    const double akp = A[(size_t)k * cols + p], akq = A[(size_t)k * cols + q];
+                    A[(size_t)k * cols + p] = c * akp - sn * akq;
+                    A[(size_t)k * cols + q] = sn * akp + c * akq;
+                }
+                for (int k = 0; k < cols; ++k) {
+                    const double apk = A[(size_t)p * cols + k], aqk = A[(size_t)q * cols + k];
+                    A[(size_t)p * cols + k] = c * apk - sn * aqk;
+                    A[(size_t)q * cols + k] = sn * apk + c * aqk;
+                }
+                for (int k = 0; k < cols; ++k) {
+                    const double vkp = V[(size_t)k * cols + p], vkq = V[(size_t)k * cols + q];
+                    V[(size_t)k * cols + p] = c * vkp - sn * vkq;
+                    V[(size_t)k * cols + q] = sn * vkp + c * vkq;
+                }
+            }
+    }
+    std::vector<int> order(cols);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return A[(size_t)a * cols + a] > A[(size_t)b * cols + b]; });
+    w.resize(cols);
+    std::vector<double> Vs((size_t)cols * cols);
+    for (int i = 0; i < cols; ++i) {
+        w[i] = std::max(A[(size_t)order[i] * cols + order[i]], 0.0);
+        for (int k = 0; k < cols; ++k) Vs[(size_t)k * cols + i] = V[(size_t)k * cols + order[i]];
+    }
+    V.swap(Vs);
+}
+
+int keep_argmax_rows(const std::vector<double> &reps, int k, int cols, int32_t *kept_out) {
+    std::vector<int32_t> kept;
+    for (int c = 0; c < k; ++c) {
+        int best = 0;
+        for (int j = 1; j < cols; ++j)
+            if (reps[(size_t)c * cols + j] > reps[(size_t)c * cols + best]) best = j;
+        kept.push_back(best);
+    }
+    std::sort(kept.begin(), kept.end());
+    kept.erase(std::unique(kept.begin(), kept.end()), kept.end());
+    std::copy(kept.begin(), kept.end(), kept_out);
+    return (int)kept.size();
+}
+
+}  // namespace
+
+extern "C" int ks_tune_prune_top_n(const double *normalised, int rows, int cols, int n,
+                                   int32_t *kept_out) {
+    if (!normalised || !kept_out || rows <= 0 || cols <= 0 || n < 1) return KS_ERR_INVALID_ARG;
+    std::vector<int> wins(cols, 0);
+    for (int s = 0; s < rows; ++s) {
+        int best = 0;
+        for (int c = 1; c < cols; ++c)
+            if (normalised[(size_t)s * cols + c] > normalised[(size_t)s * cols + best]) best = c;
+        ++wins[best];
+    }
+    std::vector<int> order(cols);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return wins[a] > wins[b]; });
+    std::vector<int32_t> kept;
+    for (int i = 0; i < cols && (int)kept.size() < n; ++i)
+        if (wins[order[i]] > 0) kept.push_back(order[i]);
+    std::sort(kept.begin(), kept.end());
+    std::copy(kept.begin(), kept.end(), kept_out);
+    return (int)kept.size();
+}
+
+extern "C" int ks_tune_prune_kmeans(const double *normalised, int rows, int cols, int n, int pca_dims,
+                                    int max_iter, int32_t *kept_out) {
+    if (!normalised || !kept_out || rows <= 0 || cols <= 0 || n < 1 || pca_dims < 0 || pca_dims > cols ||
+        max_iter < 1)
+        return KS_ERR_INVALID_ARG;
+    const int k = std::min(n, rows);
+    std::vector<double> centres;
+    if (pca_dims == 0) {
+        std::vector<double> Z(normalised, normalised + (size_t)rows * cols);
+        lloyd(Z, rows, cols, k, max_iter, centres);
+        return keep_argmax_rows(centres, k, cols, kept_out);
+    }
+    std::vector<double> mean, w, V;
+    covariance_eigen(normalised, rows, cols, mean, w, V);
+    const int d = pca_dims;
+    std::vector<double> Z((size_t)rows * d, 0.0);
+    for (int s = 0; s < rows; ++s)
+        for (int i = 0; i < d; ++i) {
+            double acc = 0.0;
+            for (int j = 0; j < cols; ++j) acc += (normalised[(size_t)s * cols + j] - mean[j]) * V[(size_t)j * cols + i];
+            Z[(size_t)s * d + i] = acc;
+        }
+    lloyd(Z, rows, d, k, max_iter, centres);
+    std::vector<double> back((size_t)k * cols);
+    for (int c = 0; c < k; ++c)
+        for (int j = 0; j < cols; ++j) {
+            double acc = mean[j];
+            for (int i = 0; i < d; ++i) acc += centres[(size_t)c * d + i] * V[(size_t)j * cols + i];
+            back[(size_t)c * cols + j] = acc;
+        }
+    return keep_argmax_rows(back, k, cols, kept_out);
+}
+
+extern "C" int ks_tune_pca_variance(const double *normalised, int rows, int cols, double *ratio_out) {
+    if (!normalised || !ratio_out || rows <= 0 || cols <= 0) return KS_ERR_INVALID_ARG;
+    std::vector<double> mean, w, V;
+    covariance_eigen(normalised, rows, cols, mean, w, V);
+    double total = 0.0;
+    for (double v : w) total += v;
+    if (!(total > 0.0)) return KS_ERR_INVALID_ARG;
+    for (int i = 0; i < cols; ++i) ratio_out[i] = w[i] / total;
+    return KS_OK;
+}
