@@ -34,6 +34,9 @@ def kernel_symbol(ks, dt, kid, tA, tB, vec=True, dma=False):
     akc, bkc = int(not tA), int(bool(tB))
     split = ki["split_k"] > 1
     b = lambda v: "true" if v else "false"
+    if dt == ks.F32 and ki["core_name"] == "direct":
+        return "gemm_f32_direct_kernel<%d, %d, %d, %d, %d, %s, %s, %s, %s>" % (
+            ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], b(split), b(akc), b(bkc), b(vec))
     if dt == ks.F32:
         p1, p2 = (ki["tm"], ki["tn"]) if ki["core_name"] == "fma" else (ki["wm"], ki["wn"])
         return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s>" % (

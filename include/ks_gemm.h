@@ -48,19 +48,22 @@ typedef enum {
 } ks_status;
 
 typedef enum { KS_F32 = 0, KS_BF16 = 1 } ks_dtype;           /* type of A and B; C is fp32 */
-typedef enum { KS_CORE_FMA = 0, KS_CORE_MFMA16 = 1, KS_CORE_MFMA32 = 2 } ks_core;
+typedef enum { KS_CORE_FMA = 0, KS_CORE_MFMA16 = 1, KS_CORE_MFMA32 = 2, KS_CORE_DIRECT = 3 } ks_core;
 
 /* One member of the kernel family (Section II: work-group tile, per-work-item tile and
  * accumulator step are the compile-time parameters of the paper's kernel). */
 typedef struct {
     int32_t id;          /* dense, 0 .. ks_num_kernels(dtype)-1; frozen */
     int32_t dtype;       /* ks_dtype */
-    int32_t core;        /* ks_core: per-lane FMA outer product, or MFMA with 16x16 / 32x32 fragments */
+    int32_t core;        /* ks_core: per-lane FMA outer product, MFMA with 16x16 / 32x32 fragments staged
+                            through LDS, or 16x16 MFMA fed from global memory directly (no LDS) */
     int32_t bm, bn, bk;  /* work-group tile rows, cols; K-step staged through LDS */
     int32_t wm, wn;      /* wave tile (MFMA cores); equals tm x tn layout unit for the FMA core */
     int32_t tm, tn;      /* per-lane register tile (FMA core) or fragments per wave (MFMA cores) */
     int32_t threads;     /* work-group size */
-    int32_t split_k;     /* number of K partitions reduced through the workspace (1 = none) */
+    int32_t split_k;     /* number of K partitions reduced through the workspace (1 = none; 0 = chosen
+                            per call: enough partitions to fill the device, fewer if the registered
+                            workspace is smaller, none without a workspace) */
     int32_t lds_bytes;   /* static LDS of the instantiation (both stages) */
 } ks_kernel_info_t;
 
@@ -164,6 +167,7 @@ int ks_calibration_copy(void *dst_device, const void *src_device, size_t bytes, 
  * atomics) need split_k * batch * M * N floats of scratch.  The caller registers one device
  * buffer per process; NULL / 0 unregisters.  Kernels with split_k == 1 never touch it. */
 int ks_set_workspace(void *device_ptr, size_t bytes);
+/* Bytes the kernel would like for this output size (for split_k == 0 the most it can use). */
 size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N, int64_t batch);
 
 /* ---------------------------------------------------------------- offline tuner (host only)

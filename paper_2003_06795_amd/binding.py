@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libks_gemm.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
-CORE_NAMES = {0: "fma", 1: "mfma16", 2: "mfma32"}
+CORE_NAMES = {0: "fma", 1: "mfma16", 2: "mfma32", 3: "direct"}
 NUM_RAW_FEATURES, NUM_FEATURES, MAX_TREE_NODES = 6, 10, 4096
 FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "min(M,N)", "max(M,N)"]
 
@@ -68,6 +68,12 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libks_gemm.so is not built: run `python -m paper_2003_06795_amd.build` "
                            "(there is no fallback path)")
+    # PyTorch owns device memory and streams here, so its HIP runtime must be the one this process
+    # uses: load it before the library (whichever copy of the runtime is loaded first serves both).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     L.ks_gemm_f32.argtypes = _GEMM
     L.ks_gemm_bf16.argtypes = _GEMM

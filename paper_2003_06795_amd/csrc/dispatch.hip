@@ -24,12 +24,12 @@ constexpr int threads_of(int core, int bm, int bn, int p1, int p2) {
 }
 
 constexpr int KS_CORE_OF_FMA = KS_CORE_FMA, KS_CORE_OF_MFMA16 = KS_CORE_MFMA16,
-              KS_CORE_OF_MFMA32 = KS_CORE_MFMA32;
+              KS_CORE_OF_MFMA32 = KS_CORE_MFMA32, KS_CORE_OF_DIRECT = KS_CORE_DIRECT;
 
 const InstanceDesc kF32[kNumF32] = {
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK)                              \
     {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), SPLITK, \
-     2 * BK * ((BM + 4) + (BN + 4)) * 4},
+     KS_CORE_OF_##CORE == KS_CORE_DIRECT ? 0 : 2 * BK * ((BM + 4) + (BN + 4)) * 4},
 #include "instances.def"
 #undef KS_F32_INSTANCE
 };
@@ -73,6 +73,14 @@ void init_tables() {
 int g_forceGeneric = 0;
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
+
+// K partitions for an instance whose split is chosen per call: enough work-groups for about
+// twelve waves on each of the 256 compute units, capped at 64.
+int64_t auto_split(const InstanceDesc *d, int64_t tiles) {
+    const int64_t target = 256 * 12 / (d->threads / 64);
+    int64_t s = target / (tiles > 0 ? tiles : 1);
+    return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
 
 const InstanceDesc *desc_of(int dtype, int id) {
     if (dtype == KS_F32) return (id >= 0 && id < kNumF32) ? &kF32[id] : nullptr;
@@ -149,6 +157,9 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
     if (M == 0 || N == 0 || batch == 0) return KS_OK;
     std::call_once(g_once, init_tables);
 
+    // An error left behind by an earlier, unrelated runtime call must not be blamed on this launch.
+    (void)hipGetLastError();
+
     if (K == 0) {
         const long long total = (long long)batch * M * N;
         const int grid = (int)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
@@ -164,8 +175,18 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
     p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = (int)batch;
     p.tilesM = (int)((M + d->bm - 1) / d->bm);
     p.tilesN = (int)((N + d->bn - 1) / d->bn);
-    p.splitK = d->splitK;
     const int64_t kTiles = (K + d->bk - 1) / d->bk;
+    p.splitK = d->splitK;
+    if (d->splitK == 0) {
+        // automatic split: as many K partitions as fill the device, at least two K-steps each,
+        // and no more than the registered workspace can hold (1 = the plain single-kernel form)
+        int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch);
+        if (s > kTiles / 2) s = kTiles / 2;
+        const size_t per = (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+        if (!g_ws) s = 1;
+        else if ((size_t)s * per > g_wsBytes) s = (int64_t)(g_wsBytes / per);
+        p.splitK = s < 1 ? 1 : (int)s;
+    }
     p.kChunk = (int)(((kTiles + p.splitK - 1) / p.splitK) * d->bk);
     p.alpha = alpha; p.beta = beta;
 
@@ -185,14 +206,15 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
     const bool vec = aligned(A, 16) && aligned(B, 16) && lda % w == 0 && ldb % w == 0 &&
                      extA % w == 0 && extB % w == 0 &&
                      (batch == 1 || (strideA % w == 0 && strideB % w == 0));
-    const int variant = (akc ? 4 : 0) + (bkc ? 2 : 0) + (vec ? 1 : 0);
+    const int splitBit = p.splitK > 1 ? 8 : 0;       // read by instances whose split is chosen per call
+    const int variant = (akc ? 4 : 0) + (bkc ? 2 : 0) + (vec ? 1 : 0) + splitBit;
 
     // bf16 fast path: operand tiles go global -> LDS directly.  Needs 16-byte accesses, whole
     // K-steps, and tile-relative byte offsets that fit 32 bits.
     const bool dma = dtype == KS_BF16 && vec && g_forceGeneric == 0 && K % d->bk == 0 &&
                      lda <= (1LL << 22) && ldb <= (1LL << 22);
     if (dma)
-        g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0), stream);
+        g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0) + splitBit, stream);
     else
         (dtype == KS_F32 ? g_f32[id] : g_bf16[id])(p, (int)grid64, variant, stream);
     if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
@@ -226,7 +248,7 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     out->dtype = dtype;
     out->core = d->core;
     out->bm = d->bm; out->bn = d->bn; out->bk = d->bk;
-    const int frag = d->core == KS_CORE_MFMA16 ? 16 : 32;
+    const int frag = d->core == KS_CORE_MFMA32 ? 32 : 16;
     if (d->core == KS_CORE_FMA) {
         out->wm = d->p1; out->wn = d->p2; out->tm = d->p1; out->tn = d->p2;
     } else {
@@ -242,6 +264,7 @@ extern "C" int ks_calibration_copy(void *dst, const void *src, size_t bytes, voi
     if (!dst || !src || bytes == 0 || bytes % 16 != 0) return KS_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16)
         return KS_ERR_INVALID_ARG;
+    (void)hipGetLastError();
     const long long n16 = (long long)(bytes / 16);
     const int grid = (int)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
     hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
@@ -268,8 +291,13 @@ extern "C" int ks_set_workspace(void *device_ptr, size_t bytes) {
 extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N,
                                             int64_t batch) {
     const InstanceDesc *d = desc_of(dtype, kernel_id);
-    if (!d || d->splitK <= 1 || M <= 0 || N <= 0 || batch <= 0) return 0;
-    return (size_t)d->splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+    if (!d || d->splitK == 1 || M <= 0 || N <= 0 || batch <= 0) return 0;
+    int64_t s = d->splitK;
+    if (s == 0) {
+        s = auto_split(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch);
+        if (s <= 1) return 0;
+    }
+    return (size_t)s * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
 }
 
 #define KS_GEMM_PASS                                                                            \

@@ -23,7 +23,7 @@
 
 namespace ks {
 
-enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2 };
+enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3 };
 
 template <int CORE, int BM, int BN, int P1, int P2>
 struct F32Shape {

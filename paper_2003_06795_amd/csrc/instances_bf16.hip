@@ -11,7 +11,7 @@
 namespace ks {
 
 template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT>
-static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t s) {
+static void launch_bf16_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     const dim3 g((unsigned)grid), b(NT);
 #define KS_V(A, B, V) hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, SPLIT, A, B, V>), g, b, 0, s, p)
@@ -28,10 +28,21 @@ static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t 
 #undef KS_V
 }
 
+// SPLITMODE 0: never split-K; 1: always; 2: decided per call (variant bit 3), both forms compiled
+template <int F, int BM, int BN, int BK, int WM, int WN, int SPLITMODE>
+static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t s) {
+    if constexpr (SPLITMODE == 2) {
+        if (variant & 8) launch_bf16_fixed<F, BM, BN, BK, WM, WN, true>(p, grid, variant & 7, s);
+        else launch_bf16_fixed<F, BM, BN, BK, WM, WN, false>(p, grid, variant & 7, s);
+    } else {
+        launch_bf16_fixed<F, BM, BN, BK, WM, WN, SPLITMODE == 1>(p, grid, variant & 7, s);
+    }
+}
+
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16<F, BM, BN, BK, WM, WN, ((SPLITK) > 1)>;
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16<F, BM, BN, BK, WM, WN, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0)>;
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 }

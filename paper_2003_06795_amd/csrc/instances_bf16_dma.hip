@@ -12,7 +12,7 @@ namespace ks {
 
 // variant = akc * 2 + bkc
 template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT>
-static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStream_t s) {
+static void launch_bf16_dma_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     const dim3 g((unsigned)grid), b(NT);
 #define KS_V(A, B) hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B>), g, b, 0, s, p)
@@ -25,10 +25,21 @@ static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStrea
 #undef KS_V
 }
 
+// SPLITMODE 0: never split-K; 1: always; 2: decided per call (variant bit 3), both forms compiled
+template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, int SPLITMODE>
+static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStream_t s) {
+    if constexpr (SPLITMODE == 2) {
+        if (variant & 8) launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, true>(p, grid, variant & 3, s);
+        else launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, false>(p, grid, variant & 3, s);
+    } else {
+        launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, SPLITMODE == 1>(p, grid, variant & 3, s);
+    }
+}
+
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16_dma<F, BM, BN, BK, WM, WN, STAGES, ((SPLITK) > 1)>;
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16_dma<F, BM, BN, BK, WM, WN, STAGES, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0)>;
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 }

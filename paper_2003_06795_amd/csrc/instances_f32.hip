@@ -1,6 +1,7 @@
 // One shard of the fp32 instantiations: compiled KS_NSHARDS times with -DKS_SHARD=0..KS_NSHARDS-1
 // so the family builds in parallel.  Each shard fills its ids of the launch table.
 #include "gemm_f32.hpp"
+#include "gemm_f32_direct.hpp"
 #include "registry.hpp"
 
 #ifndef KS_SHARD
@@ -12,10 +13,16 @@
 namespace ks {
 
 template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT>
-static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s) {
+static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads;
     const dim3 g((unsigned)grid), b(NT);
-#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p)
+#define KS_V(A, B, V)                                                                                   \
+    do {                                                                                                \
+        if constexpr (CORE == CORE_DIRECT)                                                              \
+            hipLaunchKernelGGL((gemm_f32_direct_kernel<BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p); \
+        else                                                                                            \
+            hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p);  \
+    } while (0)
     switch (variant) {
         case 0: KS_V(false, false, false); break;
         case 1: KS_V(false, false, true); break;
@@ -29,10 +36,21 @@ static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s
 #undef KS_V
 }
 
+// SPLITMODE 0: never split-K; 1: always; 2: decided per call (variant bit 3), both forms compiled
+template <int CORE, int BM, int BN, int BK, int P1, int P2, int SPLITMODE>
+static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s) {
+    if constexpr (SPLITMODE == 2) {
+        if (variant & 8) launch_f32_fixed<CORE, BM, BN, BK, P1, P2, true>(p, grid, variant & 7, s);
+        else launch_f32_fixed<CORE, BM, BN, BK, P1, P2, false>(p, grid, variant & 7, s);
+    } else {
+        launch_f32_fixed<CORE, BM, BN, BK, P1, P2, SPLITMODE == 1>(p, grid, variant & 7, s);
+    }
+}
+
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) > 1)>;
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0)>;
 #include "instances.def"
 #undef KS_F32_INSTANCE
 }

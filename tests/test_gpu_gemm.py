@@ -265,3 +265,30 @@ def test_selected_call_equals_forced_call_bitwise(gpu):
         kid = ks.select(gpu.DT[dtype], p.M, p.N, p.K, p.batch, p.transA, p.transB)
         prep_workspace(gpu, p, kid)
         assert np.array_equal(dp.run(None), dp.run(kid))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_per_call_split_k_instances_with_and_without_workspace(gpu, dtype):
+    """Instances whose K partitioning is chosen per call: long K and few tiles make them split when
+    a workspace is registered; without one they run as a single kernel.  Both meet the bound."""
+    import paper_2003_06795_amd.binding as ks
+    dt = gpu.DT[dtype]
+    auto = [k for k in ids_of(gpu, dtype) if ks.kernel_info(dt, k)["split_k"] == 0]
+    assert auto, "the family has per-call split-K members"
+    for tA, tB in LAYOUTS:
+        p = wl.make_problem(dtype, tA, tB, 136, 264, 4096, batch=1, alpha=1.0, beta=0.5, seed=17, key=tA * 2 + tB,
+                            dist="normal" if dtype == "bf16" else "uniform")
+        dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+        for kid in auto:
+            need = ks.workspace_bytes_needed(dt, kid, p.M, p.N, p.batch)
+            assert need > 0
+            gpu.ensure_workspace(need)
+            split = dp.run(kid)
+            check(p, split, ref, "%s kernel %d with workspace" % (dtype, kid))
+            assert np.array_equal(split, dp.run(kid))
+            try:
+                ks.set_workspace(None)
+                single = dp.run(kid)
+            finally:
+                gpu.ensure_workspace.__defaults__[0].clear()
+            check(p, single, ref, "%s kernel %d without workspace" % (dtype, kid))

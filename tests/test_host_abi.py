@@ -41,7 +41,7 @@ def test_registry_has_64_fp32_kernels_with_dense_ids():
             if ki["core_name"] == "fma":
                 assert ki["threads"] == (ki["bm"] // ki["tm"]) * (ki["bn"] // ki["tn"])
             else:
-                f = 16 if ki["core_name"] == "mfma16" else 32
+                f = 32 if ki["core_name"] == "mfma32" else 16
                 assert ki["wm"] == ki["tm"] * f and ki["wn"] == ki["tn"] * f
                 assert ki["threads"] == 64 * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"])
             key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"])
@@ -126,5 +126,8 @@ def test_workspace_bytes():
     assert ks.workspace_bytes_needed(ks.F32, 0, 100, 100, 2) == 0
     for i in range(ks.num_kernels(ks.BF16)):
         ki = ks.kernel_info(ks.BF16, i)
-        want = 0 if ki["split_k"] == 1 else ki["split_k"] * 2 * 100 * 50 * 4
-        assert ks.workspace_bytes_needed(ks.BF16, i, 100, 50, 2) == want
+        got = ks.workspace_bytes_needed(ks.BF16, i, 100, 50, 2)
+        if ki["split_k"] == 0:                  # chosen per call: at most 64 partitions
+            assert got % (2 * 100 * 50 * 4) == 0 and got <= 64 * 2 * 100 * 50 * 4
+        else:
+            assert got == (0 if ki["split_k"] == 1 else ki["split_k"] * 2 * 100 * 50 * 4)

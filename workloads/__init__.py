@@ -18,7 +18,7 @@ import numpy as np
 __all__ = [
     "Problem", "make_problem", "uniform_pm1", "normal_scaled", "f32_to_bf16_rne",
     "bf16_to_f32", "config1_problem", "CONFIG1_TILES", "config2_shapes", "config2_split",
-    "config2_rows", "config3_shapes", "config4_shapes", "config5_shapes", "bf16_tuning_shapes",
+    "config2_rows", "config2_extra_rows", "config3_shapes", "config4_shapes", "config5_shapes", "bf16_tuning_shapes",
     "bf16_tuning_split",
 ]
 
@@ -172,6 +172,16 @@ def config2_shapes(n=200, seed=1, lo=16, hi=4096, multiple=8):
             dims.append(min(max(q, lo), hi))
         out.append(tuple(dims))
     return out
+
+
+def config2_extra_rows(n=400, seed=11):
+    """More rows of the same distribution as config 2 (other seed), used only to train the fp32
+    selector on a larger table; never part of a held-out set."""
+    rows = []
+    for s, (M, N, K) in enumerate(config2_shapes(n, seed)):
+        for tA, tB in itertools.product((0, 1), (0, 1)):
+            rows.append((s, tA, tB, M, N, K, 1))
+    return rows
 
 
 def config2_split(n=200, seed=1, train_fraction=0.7):
