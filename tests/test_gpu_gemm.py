@@ -21,9 +21,10 @@ def gpu():
 
 
 def check(p, got, ref, what):
-    err = float(np.max(np.abs(got.astype(np.float64) - ref.astype(np.float64)))) if got.size else 0.0
+    live = ~c_padding_mask(p)
+    err = float(np.max(np.abs(got[live].astype(np.float64) - ref[live].astype(np.float64)))) if live.any() else 0.0
     tol = tolerance(p)
-    assert np.all(np.isfinite(got[~c_padding_mask(p)])), what
+    assert np.all(np.isfinite(got[live])), what
     assert err <= tol, "%s: max|diff| %.3e > tol %.3e" % (what, err, tol)
     mask = c_padding_mask(p)
     assert np.array_equal(got[mask], p.C0[mask], equal_nan=True), what + ": wrote outside C's logical entries"
@@ -292,3 +293,31 @@ def test_per_call_split_k_instances_with_and_without_workspace(gpu, dtype):
             finally:
                 gpu.ensure_workspace.__defaults__[0].clear()
             check(p, single, ref, "%s kernel %d without workspace" % (dtype, kid))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_seeded_random_small_problems_every_kernel(gpu, dtype):
+    """Brute force on tiny inputs: random sizes in [1, 70] (smaller than most tiles, so every edge
+    predicate is exercised), random paddings, batch strides, broadcast operands, alpha/beta incl. 0."""
+    import paper_2003_06795_amd.binding as ks
+    r = np.random.default_rng(2024)
+    for case in range(24):
+        M, N, K = (int(v) for v in r.integers(1, 71, 3))
+        if case % 6 == 0:
+            K = int(r.integers(1, 4)) * 128                     # direct-to-LDS eligible K for bf16
+            M, N = 8 * int(r.integers(1, 9)), 8 * int(r.integers(1, 9))
+        batch = int(r.integers(1, 4))
+        tA, tB = int(r.integers(0, 2)), int(r.integers(0, 2))
+        pad = tuple(int(v) for v in r.integers(0, 3, 3) * (8 if case % 6 == 0 else 1))
+        bpad = tuple(int(v) for v in r.integers(0, 2, 3) * 8)
+        alpha = float(r.choice([1.0, -0.5, 2.0, 0.0]))
+        beta = float(r.choice([0.0, 1.0, -1.5, 0.25]))
+        bc = (bool(r.integers(0, 2)) and batch > 1, bool(r.integers(0, 2)) and batch > 1)
+        p = wl.make_problem(dtype, tA, tB, M, N, K, batch=batch, alpha=alpha, beta=beta, seed=31, key=case,
+                            pad=pad, batch_pad=bpad, broadcast=bc, dist="normal" if dtype == "bf16" else "uniform",
+                            c_fill="nan" if beta == 0.0 else "uniform")
+        dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+        for kid in ids_of(gpu, dtype):
+            prep_workspace(gpu, p, kid)
+            check(p, dp.run(kid), ref, "%s case %d (%d x %d x %d, batch %d, tA %d tB %d) kernel %d"
+                  % (dtype, case, M, N, K, batch, tA, tB, kid))
