@@ -249,7 +249,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
         __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the MFMAs they overlap
         const char *as = S == 0 ? As0 : S == 1 ? As1 : S == 2 ? As2 : As3;
         const char *bs = S == 0 ? Bs0 : S == 1 ? Bs1 : S == 2 ? Bs2 : Bs3;
+        // waves that are issuing MFMAs go ahead of waves that are still issuing loads or waiting
+        __builtin_amdgcn_s_setprio(3);
         compute(as, bs);
+        __builtin_amdgcn_s_setprio(0);
     };
 
     if (nk > 0) issue(0, std::integral_constant<int, 0>{});
