@@ -249,8 +249,9 @@ def test_argument_errors_launch_nothing(gpu):
         ks.gemm_f32_with_kernel(**dict(base, M=2 ** 31))
     assert e.value.status == ks.ERR_UNSUPPORTED
     ks.set_workspace(None)
+    fixed_split = [k for k in range(ks.num_kernels(ks.BF16)) if ks.kernel_info(ks.BF16, k)["split_k"] > 1][0]
     with pytest.raises(ks.KsError) as e:
-        ks.gemm_bf16_with_kernel(17, 0, 0, 4, 4, 4, 1.0, A, 4, A, 4, 0.0, C, 4)
+        ks.gemm_bf16_with_kernel(fixed_split, 0, 0, 4, 4, 4, 1.0, A, 4, A, 4, 0.0, C, 4)
     assert e.value.status == ks.ERR_WORKSPACE
     torch.cuda.synchronize()
     assert torch.all(C == 7.0)
