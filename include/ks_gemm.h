@@ -48,7 +48,9 @@ typedef enum {
 } ks_status;
 
 typedef enum { KS_F32 = 0, KS_BF16 = 1 } ks_dtype;           /* type of A and B; C is fp32 */
-typedef enum { KS_CORE_FMA = 0, KS_CORE_MFMA16 = 1, KS_CORE_MFMA32 = 2, KS_CORE_DIRECT = 3 } ks_core;
+typedef enum {
+    KS_CORE_FMA = 0, KS_CORE_MFMA16 = 1, KS_CORE_MFMA32 = 2, KS_CORE_DIRECT = 3, KS_CORE_KSLICE = 4
+} ks_core;
 
 /* One member of the kernel family (Section II: work-group tile, per-work-item tile and
  * accumulator step are the compile-time parameters of the paper's kernel). */
@@ -56,7 +58,8 @@ typedef struct {
     int32_t id;          /* dense, 0 .. ks_num_kernels(dtype)-1; frozen */
     int32_t dtype;       /* ks_dtype */
     int32_t core;        /* ks_core: per-lane FMA outer product, MFMA with 16x16 / 32x32 fragments staged
-                            through LDS, or 16x16 MFMA fed from global memory directly (no LDS) */
+                            through LDS, 16x16 MFMA fed from global memory directly (no LDS), or the
+                            same with the K range of a work-group cut into one slice per wave */
     int32_t bm, bn, bk;  /* work-group tile rows, cols; K-step staged through LDS */
     int32_t wm, wn;      /* wave tile (MFMA cores); equals tm x tn layout unit for the FMA core */
     int32_t tm, tn;      /* per-lane register tile (FMA core) or fragments per wave (MFMA cores) */
@@ -65,6 +68,8 @@ typedef struct {
                             per call: enough partitions to fill the device, fewer if the registered
                             workspace is smaller, none without a workspace) */
     int32_t lds_bytes;   /* static LDS of the instantiation (both stages) */
+    int32_t k_waves;     /* K slices inside one work-group, one wave each, summed through LDS
+                            (core KS_CORE_KSLICE; 1 for every other core) */
 } ks_kernel_info_t;
 
 /* Node of a deployed decision tree (Section IV: nested integer comparisons).

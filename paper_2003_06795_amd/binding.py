@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libks_gemm.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
-CORE_NAMES = {0: "fma", 1: "mfma16", 2: "mfma32", 3: "direct"}
+CORE_NAMES = {0: "fma", 1: "mfma16", 2: "mfma32", 3: "direct", 4: "kslice"}
 NUM_RAW_FEATURES, NUM_FEATURES, MAX_TREE_NODES = 6, 10, 4096
 FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "min(M,N)", "max(M,N)"]
 
@@ -23,7 +23,7 @@ FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "mi
 class KernelInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("id", "dtype", "core", "bm", "bn", "bk", "wm", "wn", "tm", "tn", "threads",
-                 "split_k", "lds_bytes")]
+                 "split_k", "lds_bytes", "k_waves")]
 
     def as_dict(self):
         d = {n: int(getattr(self, n)) for n, _ in self._fields_}

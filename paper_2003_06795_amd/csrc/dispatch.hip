@@ -20,16 +20,18 @@ KS_DECL(8) KS_DECL(9) KS_DECL(10) KS_DECL(11) KS_DECL(12) KS_DECL(13) KS_DECL(14
 namespace {
 
 constexpr int threads_of(int core, int bm, int bn, int p1, int p2) {
-    return core == KS_CORE_FMA ? (bm / p1) * (bn / p2) : 64 * (bm / p1) * (bn / p2);
+    return core == KS_CORE_FMA ? (bm / p1) * (bn / p2) : core == KS_CORE_KSLICE ? 64 * p1 * (bm / p2) * (bn / p2) : 64 * (bm / p1) * (bn / p2);
 }
 
 constexpr int KS_CORE_OF_FMA = KS_CORE_FMA, KS_CORE_OF_MFMA16 = KS_CORE_MFMA16,
-              KS_CORE_OF_MFMA32 = KS_CORE_MFMA32, KS_CORE_OF_DIRECT = KS_CORE_DIRECT;
+              KS_CORE_OF_MFMA32 = KS_CORE_MFMA32, KS_CORE_OF_DIRECT = KS_CORE_DIRECT,
+              KS_CORE_OF_KSLICE = KS_CORE_KSLICE;
 
 const InstanceDesc kF32[kNumF32] = {
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK)                              \
     {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), SPLITK, \
-     KS_CORE_OF_##CORE == KS_CORE_DIRECT ? 0 : 2 * BK * ((BM + 4) + (BN + 4)) * 4},
+     KS_CORE_OF_##CORE == KS_CORE_DIRECT ? 0 : KS_CORE_OF_##CORE == KS_CORE_KSLICE ? P1 * BM * BN * 4 \
+                                             : 2 * BK * ((BM + 4) + (BN + 4)) * 4},
 #include "instances.def"
 #undef KS_F32_INSTANCE
 };
@@ -74,12 +76,29 @@ int g_forceGeneric = 0;
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
-// K partitions for an instance whose split is chosen per call: enough work-groups for about
-// twelve waves on each of the 256 compute units, capped at 64.
-int64_t auto_split(const InstanceDesc *d, int64_t tiles) {
-    const int64_t target = 256 * 12 / (d->threads / 64);
-    int64_t s = target / (tiles > 0 ? tiles : 1);
+// K partitions for an instance whose split is chosen per call.  Work-groups run in rounds of
+// `slots` (256 compute units times the work-groups that fit one, taken as twelve waves per unit);
+// a work-group costs its K-steps plus a fixed prologue/epilogue, and splitting adds the reduction
+// pass.  The cheapest count wins (the smaller one on ties); never more than 64, never more than
+// fills one round, and at least two K-steps per partition.
+int64_t auto_split_max(const InstanceDesc *d, int64_t tiles) {
+    const int64_t waves = d->threads / 64;
+    const int64_t slots = 256 * (12 / waves > 0 ? 12 / waves : 1);
+    const int64_t s = (slots + tiles - 1) / (tiles > 0 ? tiles : 1);
     return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+
+int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles) {
+    const int64_t waves = d->threads / 64;
+    const int64_t slots = 256 * (12 / waves > 0 ? 12 / waves : 1);
+    int64_t best = 1, bestCost = -1;
+    const int64_t smax = auto_split_max(d, tiles);
+    for (int64_t s = 1; s <= smax && (s == 1 || 2 * s <= kTiles); ++s) {
+        const int64_t rounds = (tiles * s + slots - 1) / slots;
+        const int64_t cost = rounds * ((kTiles + s - 1) / s + 6) + (s > 1 ? 10 : 0);
+        if (bestCost < 0 || cost < bestCost) { bestCost = cost; best = s; }
+    }
+    return best;
 }
 
 const InstanceDesc *desc_of(int dtype, int id) {
@@ -106,6 +125,28 @@ __global__ void copy_kernel(const floatx4 *src, floatx4 *dst, long long n16) {
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n16;
          i += (long long)gridDim.x * blockDim.x)
         dst[i] = src[i];
+}
+
+// Split-K second pass, four consecutive entries of a row per lane (N, ldc, strideC multiples of 4;
+// ws and C 16-byte aligned).  Each entry is summed in the same order as in the scalar form.
+__global__ void splitk_reduce4_kernel(const float *ws, float *C, long long ldc, long long strideC, int M,
+                                      int N, int batch, int splitK, float alpha, float beta) {
+    const long long per = (long long)batch * M * N, per4 = per >> 2;
+    for (long long q = blockIdx.x * (long long)blockDim.x + threadIdx.x; q < per4;
+         q += (long long)gridDim.x * blockDim.x) {
+        const long long i = q << 2;
+        floatx4 acc = *reinterpret_cast<const floatx4 *>(ws + i);
+        for (int s = 1; s < splitK; ++s) acc += *reinterpret_cast<const floatx4 *>(ws + (long long)s * per + i);
+        const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
+        floatx4 *c = reinterpret_cast<floatx4 *>(C + b * strideC + (r / N) * ldc + (r % N));
+        floatx4 v = alpha * acc;
+        if (beta != 0.0f) {
+            const floatx4 c0 = *c;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = fmaf(beta, c0[e], alpha * acc[e]);
+        }
+        *c = v;
+    }
 }
 
 // Split-K second pass: C = alpha * (ws[0] + ws[1] + ... in this fixed order) + beta * C
@@ -180,8 +221,8 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
     if (d->splitK == 0) {
         // automatic split: as many K partitions as fill the device, at least two K-steps each,
         // and no more than the registered workspace can hold (1 = the plain single-kernel form)
-        int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch);
-        if (s > kTiles / 2) s = kTiles / 2;
+        const int64_t steps = d->core == KS_CORE_KSLICE ? (kTiles + d->p1 - 1) / d->p1 : kTiles;
+        int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch, steps);
         const size_t per = (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
         if (!g_ws) s = 1;
         else if ((size_t)s * per > g_wsBytes) s = (int64_t)(g_wsBytes / per);
@@ -221,10 +262,13 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
 
     if (p.splitK > 1) {
         const long long total = (long long)batch * M * N;
-        const int grid = (int)((total + 255) / 256 < 1048576 ? (total + 255) / 256 : 1048576);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(grid), dim3(256), 0, stream, p.ws, C,
-                           (long long)ldc, (long long)strideC, (int)M, (int)N, (int)batch, p.splitK,
-                           alpha, beta);
+        const bool vec4 = N % 4 == 0 && ldc % 4 == 0 && aligned(C, 16) && aligned(p.ws, 16) &&
+                          (batch == 1 || strideC % 4 == 0);
+        const long long units = vec4 ? total / 4 : total;
+        const int grid = (int)((units + 255) / 256 < 1048576 ? (units + 255) / 256 : 1048576);
+        hipLaunchKernelGGL(vec4 ? splitk_reduce4_kernel : splitk_reduce_kernel, dim3(grid), dim3(256), 0,
+                           stream, p.ws, C, (long long)ldc, (long long)strideC, (int)M, (int)N, (int)batch,
+                           p.splitK, alpha, beta);
         if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
     }
     return KS_OK;
@@ -251,9 +295,12 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     const int frag = d->core == KS_CORE_MFMA32 ? 32 : 16;
     if (d->core == KS_CORE_FMA) {
         out->wm = d->p1; out->wn = d->p2; out->tm = d->p1; out->tn = d->p2;
+    } else if (d->core == KS_CORE_KSLICE) {
+        out->wm = d->p2; out->wn = d->p2; out->tm = d->p2 / 16; out->tn = d->p2 / 16;
     } else {
         out->wm = d->p1; out->wn = d->p2; out->tm = d->p1 / frag; out->tn = d->p2 / frag;
     }
+    out->k_waves = d->core == KS_CORE_KSLICE ? d->p1 : 1;
     out->threads = d->threads;
     out->split_k = d->splitK;
     out->lds_bytes = d->ldsBytes;
@@ -294,7 +341,7 @@ extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M,
     if (!d || d->splitK == 1 || M <= 0 || N <= 0 || batch <= 0) return 0;
     int64_t s = d->splitK;
     if (s == 0) {
-        s = auto_split(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch);
+        s = auto_split_max(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch);
         if (s <= 1) return 0;
     }
     return (size_t)s * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);

@@ -23,12 +23,22 @@
 
 namespace ks {
 
-enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3 };
+// Staging-register sets (K-steps in flight) as a function of the registers one set takes and the
+// work-group size.  Measured on the small-problem workload: depth 4 gains 5 - 8 % for 8-register
+// sets and 2 - 3 % for 16-register sets of four-wave work-groups, but costs 2 % for the eight-wave
+// 128 x 128 x 32 tile, which already has two waves per SIMD to cover the latency; odd depths lose
+// (the LDS buffer of a step is then no longer fixed inside the unrolled body).
+#ifndef KS_F32_PREFETCH
+#define KS_F32_PREFETCH(regs, threads) \
+    ((regs) <= 8 || ((regs) <= 16 && (threads) <= 256) ? 4 : (regs) <= 32 ? 2 : 1)
+#endif
+
+enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3, CORE_KSLICE = 4 };
 
 template <int CORE, int BM, int BN, int P1, int P2>
 struct F32Shape {
     static constexpr int threads =
-        CORE == CORE_FMA ? (BM / P1) * (BN / P2) : 64 * (BM / P1) * (BN / P2);
+        CORE == CORE_FMA ? (BM / P1) * (BN / P2) : CORE == CORE_KSLICE ? 64 * P1 * (BM / P2) * (BN / P2) : 64 * (BM / P1) * (BN / P2);
     static constexpr int frag = CORE == CORE_MFMA16 ? 16 : 32;
 };
 
@@ -120,8 +130,15 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
     const int kEnd = min(p.K, kBegin + p.kChunk);
     const int nk = (kEnd - kBegin + BK - 1) / BK;
 
-    TileLoader<BM, BK, NT, AKC, VEC> la;
-    TileLoader<BN, BK, NT, BKC, VEC> lb;
+    // K-steps in flight between global memory and LDS (each in its own set of staging registers):
+    // small tiles are latency-bound - few waves per compute unit, short MFMA runs per K-step - and
+    // afford several; large tiles hide the latency behind their MFMAs and keep the registers.
+    using LoaderA = TileLoader<BM, BK, NT, AKC, VEC>;
+    using LoaderB = TileLoader<BN, BK, NT, BKC, VEC>;
+    constexpr int STAGE_REGS = (LoaderA::ITERS + LoaderB::ITERS) * LoaderA::W;
+    constexpr int PF = KS_F32_PREFETCH(STAGE_REGS, NT);
+    LoaderA la[PF];
+    LoaderB lb[PF];
 
     // accumulators
     constexpr int FR = Shape::frag;
@@ -159,23 +176,8 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
         subN = (wave % (BN / P2)) * P2;
     }
 
-    if (nk > 0) {
-        la.load(Ab, p.lda, row0, p.M, kBegin, kEnd, tid);
-        lb.load(Bb, p.ldb, col0, p.N, kBegin, kEnd, tid);
-        la.store(As[0], tid);
-        lb.store(Bs[0], tid);
-    }
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) {
-            const int k0 = kBegin + (kt + 1) * BK;
-            la.load(Ab, p.lda, row0, p.M, k0, kEnd, tid);
-            lb.load(Bb, p.ldb, col0, p.N, k0, kEnd, tid);
-        }
-        const float *as = As[cur], *bs = Bs[cur];
+    // one K-step of MFMAs / FMAs on a landed LDS stage
+    auto compute_step = [&](const float *as, const float *bs) {
         if constexpr (CORE == CORE_FMA) {
 #pragma unroll
             for (int kk = 0; kk < BK; ++kk) {
@@ -222,11 +224,41 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
                         acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc32[i][j], 0, 0, 0);
             }
         }
-        if (more) {
-            la.store(As[cur ^ 1], tid);
-            lb.store(Bs[cur ^ 1], tid);
+    };
+
+#pragma unroll
+    for (int d = 0; d < PF; ++d)
+        if (d < nk) {
+            la[d].load(Ab, p.lda, row0, p.M, kBegin + d * BK, kEnd, tid);
+            lb[d].load(Bb, p.ldb, col0, p.N, kBegin + d * BK, kEnd, tid);
         }
-        __syncthreads();
+    if (nk > 0) {
+        la[0].store(As[0], tid);
+        lb[0].store(Bs[0], tid);
+    }
+    __syncthreads();
+
+    // K-step kt sits in LDS buffer kt & 1 and came through staging set kt % PF; while it is being
+    // consumed, that set is refilled with step kt + PF and step kt + 1 moves from its set to LDS.
+    for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int kt = kt0 + u;
+            if (kt >= nk) break;
+            const int cur = kt & 1;
+            if (kt + PF < nk) {
+                const int k0 = kBegin + (kt + PF) * BK;
+                la[u].load(Ab, p.lda, row0, p.M, k0, kEnd, tid);
+                lb[u].load(Bb, p.ldb, col0, p.N, k0, kEnd, tid);
+            }
+            const float *as = As[cur], *bs = Bs[cur];
+            compute_step(as, bs);
+            if (kt + 1 < nk) {
+                la[(u + 1) % PF].store(As[cur ^ 1], tid);
+                lb[(u + 1) % PF].store(Bs[cur ^ 1], tid);
+            }
+            __syncthreads();
+        }
     }
 
     // epilogue

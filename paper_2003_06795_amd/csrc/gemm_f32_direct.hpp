@@ -19,6 +19,13 @@
 #pragma once
 #include "ks_common.hpp"
 
+#ifndef KS_F32_DIRECT_SETS
+// Two sets (one K-step in flight) for every tile: three and four sets were measured 1 - 5 % slower
+// on the small-problem workload (more registers, fewer resident waves) and much slower for the
+// 16-wave K-sliced members, whose register budget is 128 per lane.
+#define KS_F32_DIRECT_SETS(regs) 2
+#endif
+
 namespace ks {
 
 template <bool KC, bool VEC>
@@ -68,7 +75,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_f32_direct_ke
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    floatx4 a[2][NG][FM], b[2][NG][FN];
+    // register sets = K-steps in flight + the one being consumed; small sets afford more
+    constexpr int SET_REGS = 4 * NG * (FM + FN);
+    constexpr int S = KS_F32_DIRECT_SETS(SET_REGS);
+    floatx4 a[S][NG][FM], b[S][NG][FN];
     auto fetch = [&](int set, int k0) {
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -93,15 +103,20 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_f32_direct_ke
                                                                          acc[i][j], 0, 0, 0);
     };
 
-    if (nk > 0) fetch(0, kBegin);
-    int t = 0;
-    for (; t + 2 <= nk; t += 2) {
-        fetch(1, kBegin + (t + 1) * BK);
-        mfmas(0);
-        fetch(0, kBegin + (t + 2) * BK);         // past the end on the last trip: reads as zero, not used
-        mfmas(1);
+#pragma unroll
+    for (int d = 0; d < S - 1; ++d)
+        if (d < nk) fetch(d, kBegin + d * BK);
+    // step t lives in set t % S; while it is consumed, the set that step t - 1 left is refilled
+    // with step t + S - 1
+    for (int t0 = 0; t0 < nk; t0 += S) {
+#pragma unroll
+        for (int u = 0; u < S; ++u) {
+            const int t = t0 + u;
+            if (t >= nk) break;
+            if (t + S - 1 < nk) fetch((u + S - 1) % S, kBegin + (t + S - 1) * BK);
+            mfmas(u);
+        }
     }
-    if (t < nk) mfmas(0);
 
     write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0, col0, lane, acc);
 }

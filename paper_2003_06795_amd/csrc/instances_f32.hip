@@ -2,6 +2,7 @@
 // so the family builds in parallel.  Each shard fills its ids of the launch table.
 #include "gemm_f32.hpp"
 #include "gemm_f32_direct.hpp"
+#include "gemm_f32_kslice.hpp"
 #include "registry.hpp"
 
 #ifndef KS_SHARD
@@ -18,7 +19,9 @@ static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStre
     const dim3 g((unsigned)grid), b(NT);
 #define KS_V(A, B, V)                                                                                   \
     do {                                                                                                \
-        if constexpr (CORE == CORE_DIRECT)                                                              \
+        if constexpr (CORE == CORE_KSLICE)                                                              \
+            hipLaunchKernelGGL((gemm_f32_kslice_kernel<BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p); \
+        else if constexpr (CORE == CORE_DIRECT)                                                         \
             hipLaunchKernelGGL((gemm_f32_direct_kernel<BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p); \
         else                                                                                            \
             hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p);  \

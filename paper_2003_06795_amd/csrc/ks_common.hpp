@@ -81,35 +81,97 @@ __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord 
     }
 }
 
+// Where an accumulator tile goes: the matrix C (alpha, beta applied) or, in a split-K
+// instantiation, this partition's slice of the workspace (raw partial sums, dense rows of N).
+struct OutTarget {
+    float *base;
+    long long ld;
+    float alpha, beta;
+    int M, N;
+};
+
+template <bool SPLIT>
+__device__ __forceinline__ OutTarget out_target(const GemmParams &p, const TileCoord &tc, float *Cb) {
+    OutTarget o;
+    o.M = p.M; o.N = p.N;
+    if constexpr (SPLIT) {
+        o.base = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)p.M * p.N;
+        o.ld = p.N; o.alpha = 1.0f; o.beta = 0.0f;
+    } else {
+        o.base = Cb; o.ld = p.ldc; o.alpha = p.alpha; o.beta = p.beta;
+    }
+    return o;
+}
+
+// One lane's share of an MFMA fragment: NE values in one column `col`, at rows r0 + rowOff(e).
+// `full` (the same for every lane of the wave) says the whole fragment lies inside the matrix:
+// then there is no per-element test, and with beta != 0 all the old values are fetched before the
+// first one is needed.  Edge fragments test every element.
+template <bool SPLIT, int NE, class RowOff>
+__device__ __forceinline__ void store_lane_column(const OutTarget &o, int r0, int col, bool full,
+                                                  const float (&v)[NE], RowOff rowOff) {
+    float *ptr = o.base + (long long)r0 * o.ld + col;
+    if (full) {
+        if (SPLIT) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) ptr[(long long)rowOff(e) * o.ld] = v[e];
+        } else if (o.beta == 0.0f) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) ptr[(long long)rowOff(e) * o.ld] = o.alpha * v[e];
+        } else {
+            float old[NE];
+#pragma unroll
+            for (int e = 0; e < NE; ++e) old[e] = ptr[(long long)rowOff(e) * o.ld];
+#pragma unroll
+            for (int e = 0; e < NE; ++e) ptr[(long long)rowOff(e) * o.ld] = fmaf(o.beta, old[e], o.alpha * v[e]);
+        }
+    } else if (col < o.N) {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            if (r0 + rowOff(e) < o.M) {
+                float *c = ptr + (long long)rowOff(e) * o.ld;
+                if (SPLIT) *c = v[e];
+                else if (o.beta == 0.0f) *c = o.alpha * v[e];
+                else *c = fmaf(o.beta, *c, o.alpha * v[e]);
+            }
+        }
+    }
+}
+
 // accumulator register e of lane l of a 16x16 MFMA fragment holds C[4*(l/16) + e][l%16]
 template <bool SPLIT, int FM, int FN, class Acc>
 __device__ __forceinline__ void write_tile_mfma16(const GemmParams &p, const TileCoord &tc, float *Cb,
                                                   int rowBase, int colBase, int lane, const Acc &acc) {
-    write_tile<SPLIT>(p, tc, Cb, [&](auto emit) {
+    const OutTarget o = out_target<SPLIT>(p, tc, Cb);
+    const int rb = __builtin_amdgcn_readfirstlane(rowBase), cb = __builtin_amdgcn_readfirstlane(colBase);
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    emit(rowBase + i * 16 + 4 * (lane >> 4) + e, colBase + j * 16 + (lane & 15), acc[i][j][e]);
-    });
+        for (int j = 0; j < FN; ++j) {
+            const bool full = rb + i * 16 + 16 <= o.M && cb + j * 16 + 16 <= o.N;
+            const float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+            store_lane_column<SPLIT, 4>(o, rb + i * 16 + 4 * (lane >> 4), cb + j * 16 + (lane & 15), full, v,
+                                        [](int e) { return e; });
+        }
 }
 
 // accumulator register e of lane l of a 32x32 MFMA fragment holds C[8*(e/4) + 4*(l/32) + e%4][l%32]
 template <bool SPLIT, int FM, int FN, class Acc>
 __device__ __forceinline__ void write_tile_mfma32(const GemmParams &p, const TileCoord &tc, float *Cb,
                                                   int rowBase, int colBase, int lane, const Acc &acc) {
-    write_tile<SPLIT>(p, tc, Cb, [&](auto emit) {
+    const OutTarget o = out_target<SPLIT>(p, tc, Cb);
+    const int rb = __builtin_amdgcn_readfirstlane(rowBase), cb = __builtin_amdgcn_readfirstlane(colBase);
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+        for (int j = 0; j < FN; ++j) {
+            const bool full = rb + i * 32 + 32 <= o.M && cb + j * 32 + 32 <= o.N;
+            float v[16];
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    emit(rowBase + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3),
-                         colBase + j * 32 + (lane & 31), acc[i][j][e]);
-    });
+            for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+            store_lane_column<SPLIT, 16>(o, rb + i * 32 + 4 * (lane >> 5), cb + j * 32 + (lane & 31), full, v,
+                                         [](int e) { return 8 * (e >> 2) + (e & 3); });
+        }
 }
 
 }  // namespace ks

@@ -38,13 +38,18 @@ def test_registry_has_64_fp32_kernels_with_dense_ids():
             assert ki["id"] == i and ki["dtype"] == dt
             assert ki["lds_bytes"] <= 160 * 1024 and ki["threads"] in (64, 128, 256, 512, 1024)
             assert ki["bm"] % ki["wm"] == 0 and ki["bn"] % ki["wn"] == 0
+            assert ki["k_waves"] >= 1 and (ki["k_waves"] == 1) == (ki["core_name"] != "kslice")
             if ki["core_name"] == "fma":
                 assert ki["threads"] == (ki["bm"] // ki["tm"]) * (ki["bn"] // ki["tn"])
+            elif ki["core_name"] == "kslice":
+                assert ki["wm"] == ki["wn"] == 16 * ki["tm"] == 16 * ki["tn"]
+                assert ki["threads"] == 64 * ki["k_waves"] * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"])
+                assert ki["lds_bytes"] == ki["k_waves"] * ki["bm"] * ki["bn"] * 4
             else:
                 f = 32 if ki["core_name"] == "mfma32" else 16
                 assert ki["wm"] == ki["tm"] * f and ki["wn"] == ki["tn"] * f
                 assert ki["threads"] == 64 * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"])
-            key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"])
+            key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"], ki["k_waves"])
             assert key not in seen, "duplicate instantiation %s" % (key,)
             seen.add(key)
     with pytest.raises(ks.KsError):
