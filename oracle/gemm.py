@@ -31,6 +31,10 @@ def lib():
             f = getattr(L, name)
             f.argtypes = head
             f.restype = ctypes.c_int
+        for name in ("oracle_gemm_bias_f32", "oracle_gemm_bias_bf16"):
+            f = getattr(L, name)
+            f.argtypes = head + [_ptr]
+            f.restype = ctypes.c_int
         for name in ("oracle_gemm_f32_entries", "oracle_gemm_bf16_entries"):
             f = getattr(L, name)
             f.argtypes = head + [_i64, _ptr, _ptr, _ptr, _ptr]
@@ -70,6 +74,26 @@ def gemm(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
             batch, strideA, strideB, strideC)
     if rc != 0:
         raise ValueError("oracle gemm: invalid arguments")
+    return C
+
+
+def gemm_bias(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, bias,
+              batch=1, strideA=0, strideB=0, strideC=0):
+    """gemm() with a length-N fp32 vector added to every row: alpha*op(A)*op(B) + beta*C + bias[j]
+    (fully-connected layer, Section II-A), summed in fp64 and rounded once.  In place on C."""
+    in_t = np.float32 if dtype == "f32" else np.uint16
+    _check_in(A, in_t)
+    _check_in(B, in_t)
+    _check_in(C, np.float32)
+    if bias is not None:
+        _check_in(bias, np.float32)
+        if bias.size < N:
+            raise ValueError("bias shorter than N")
+    fn = lib().oracle_gemm_bias_f32 if dtype == "f32" else lib().oracle_gemm_bias_bf16
+    rc = fn(int(transA), int(transB), M, N, K, alpha, _p(A), lda, _p(B), ldb, beta, _p(C), ldc,
+            batch, strideA, strideB, strideC, _p(bias))
+    if rc != 0:
+        raise ValueError("oracle gemm_bias: invalid arguments")
     return C
 
 

@@ -23,6 +23,11 @@
  *   - alpha == 0 gets no special case: 0 * acc is computed.
  *   - bf16 operands are widened exactly (bf16 is the top 16 bits of an fp32).
  *   - the fp64 value alpha*acc + beta*c0 is rounded once to fp32 on store.
+ *   - the *_bias entry points add a length-N fp32 vector to every row of every
+ *     batch item, out[b][i][j] = alpha*acc + beta*c0 + bias[j]: the bias of a
+ *     fully-connected layer whose weights are op(B) (Section II-A lists
+ *     fully-connected layers among the sources of the GEMM shapes).  The sum is
+ *     formed in fp64 and still rounded once.  bias == NULL adds nothing.
  *
  * Returns 0, or -1 on an argument that makes the definition meaningless.
  */
@@ -70,7 +75,7 @@ static double dot_entry(widen_fn w, int transA, int transB, int64_t K,
 static int gemm_any(widen_fn w, int transA, int transB, int64_t M, int64_t N, int64_t K,
                     float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
                     float beta, float *C, int64_t ldc, int64_t batch,
-                    int64_t strideA, int64_t strideB, int64_t strideC) {
+                    int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
     if (check_args(transA, transB, M, N, K, lda, ldb, ldc, batch)) return -1;
     if (M == 0 || N == 0 || batch == 0) return 0;
     int64_t rows = batch * M;
@@ -83,6 +88,7 @@ static int gemm_any(widen_fn w, int transA, int transB, int64_t M, int64_t N, in
             float *c = C + b * strideC + i * ldc + j;
             double out = (double)alpha * acc;
             if (beta != 0.0f) out += (double)beta * (double)*c;
+            if (bias) out += (double)bias[j];
             *c = (float)out;
         }
     }
@@ -94,7 +100,15 @@ int oracle_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
                     float beta, float *C, int64_t ldc, int64_t batch,
                     int64_t strideA, int64_t strideB, int64_t strideC) {
     return gemm_any(widen_f32, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
-                    batch, strideA, strideB, strideC);
+                    batch, strideA, strideB, strideC, NULL);
+}
+
+int oracle_gemm_bias_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                         float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                         float beta, float *C, int64_t ldc, int64_t batch,
+                         int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
+    return gemm_any(widen_f32, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                    batch, strideA, strideB, strideC, bias);
 }
 
 int oracle_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
@@ -102,7 +116,15 @@ int oracle_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
                      float beta, float *C, int64_t ldc, int64_t batch,
                      int64_t strideA, int64_t strideB, int64_t strideC) {
     return gemm_any(widen_bf16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
-                    batch, strideA, strideB, strideC);
+                    batch, strideA, strideB, strideC, NULL);
+}
+
+int oracle_gemm_bias_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                          float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                          float beta, float *C, int64_t ldc, int64_t batch,
+                          int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
+    return gemm_any(widen_bf16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                    batch, strideA, strideB, strideC, bias);
 }
 
 /*
