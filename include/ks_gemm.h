@@ -120,6 +120,18 @@ int ks_gemm_bf16_with_kernel(int kernel_id, int transA, int transB, int64_t M, i
                              int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
                              void *stream);
 
+/* Fully-connected layer form (Section II-A names fully-connected layers among the sources of the
+ * GEMMs): C_b = alpha * op(A_b) * op(B_b) + beta * C_b + 1 * bias^T, i.e. bias[j] is added to column
+ * j of every row of every batch item after the alpha / beta step, inside the kernel's epilogue
+ * (inside the reduction pass for split-K members).  bias: device, N floats, read-only, may be
+ * NULL (then exactly ks_gemm_*).  dtype: ks_dtype of A and B.  kernel_id < 0: the deployed tree
+ * selects; otherwise that instantiation runs.  Other arguments, statuses and ownership as for
+ * ks_gemm_f32 / ks_gemm_bf16. */
+int ks_gemm_bias(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                 float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                 float beta, float *C, int64_t ldc, const float *bias,
+                 int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+
 /* Brute-force timing of one (workload, instantiation) cell (Section II-A: runtime recorded over a
  * number of iterations).  Runs `warmup` untimed launches, then `iters` samples; a sample is
  * `reps` back-to-back launches bracketed by one pair of HIP events on `stream`.  Synchronises and

@@ -107,15 +107,16 @@ const InstanceDesc *desc_of(int dtype, int id) {
     return nullptr;
 }
 
-// C = beta * C for K == 0 (C is not read when beta == 0)
+// C = beta * C (+ bias) for K == 0 (C is not read when beta == 0)
 __global__ void scale_c_kernel(float *C, long long ldc, long long strideC, int M, int N, int batch,
-                               float beta) {
+                               float beta, const float *bias) {
     const long long total = (long long)batch * M * N;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
         const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
         float *c = C + b * strideC + (r / N) * ldc + (r % N);
-        *c = beta == 0.0f ? 0.0f : beta * *c;
+        const float v = beta == 0.0f ? 0.0f : beta * *c;
+        *c = bias ? v + bias[r % N] : v;
     }
 }
 
@@ -130,7 +131,8 @@ __global__ void copy_kernel(const floatx4 *src, floatx4 *dst, long long n16) {
 // Split-K second pass, four consecutive entries of a row per lane (N, ldc, strideC multiples of 4;
 // ws and C 16-byte aligned).  Each entry is summed in the same order as in the scalar form.
 __global__ void splitk_reduce4_kernel(const float *ws, float *C, long long ldc, long long strideC, int M,
-                                      int N, int batch, int splitK, float alpha, float beta) {
+                                      int N, int batch, int splitK, float alpha, float beta,
+                                      const float *bias) {
     const long long per = (long long)batch * M * N, per4 = per >> 2;
     for (long long q = blockIdx.x * (long long)blockDim.x + threadIdx.x; q < per4;
          q += (long long)gridDim.x * blockDim.x) {
@@ -145,13 +147,18 @@ __global__ void splitk_reduce4_kernel(const float *ws, float *C, long long ldc, 
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = fmaf(beta, c0[e], alpha * acc[e]);
         }
+        if (bias) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += bias[r % N + e];
+        }
         *c = v;
     }
 }
 
-// Split-K second pass: C = alpha * (ws[0] + ws[1] + ... in this fixed order) + beta * C
+// Split-K second pass: C = alpha * (ws[0] + ws[1] + ... in this fixed order) + beta * C (+ bias)
 __global__ void splitk_reduce_kernel(const float *ws, float *C, long long ldc, long long strideC, int M,
-                                     int N, int batch, int splitK, float alpha, float beta) {
+                                     int N, int batch, int splitK, float alpha, float beta,
+                                     const float *bias) {
     const long long per = (long long)batch * M * N;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < per;
          i += (long long)gridDim.x * blockDim.x) {
@@ -161,6 +168,7 @@ __global__ void splitk_reduce_kernel(const float *ws, float *C, long long ldc, l
         float *c = C + b * strideC + (r / N) * ldc + (r % N);
         float v = alpha * acc;
         if (beta != 0.0f) v = fmaf(beta, *c, v);
+        if (bias) v += bias[r % N];
         *c = v;
     }
 }
@@ -190,7 +198,8 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
         const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
-        int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream) {
+        int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
+        const float *bias = nullptr) {
     const InstanceDesc *d = desc_of(dtype, id);
     if (!d) return KS_ERR_INVALID_ARG;
     const int rc = validate(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, batch, strideC);
@@ -205,12 +214,12 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
         const long long total = (long long)batch * M * N;
         const int grid = (int)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
         hipLaunchKernelGGL(scale_c_kernel, dim3(grid), dim3(256), 0, stream, C, (long long)ldc,
-                           (long long)strideC, (int)M, (int)N, (int)batch, beta);
+                           (long long)strideC, (int)M, (int)N, (int)batch, beta, bias);
         return hipGetLastError() == hipSuccess ? KS_OK : KS_ERR_LAUNCH;
     }
 
     GemmParams p;
-    p.A = A; p.B = B; p.C = C; p.ws = nullptr;
+    p.A = A; p.B = B; p.C = C; p.ws = nullptr; p.bias = bias;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.strideA = strideA; p.strideB = strideB; p.strideC = strideC;
     p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = (int)batch;
@@ -268,7 +277,7 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
         const int grid = (int)((units + 255) / 256 < 1048576 ? (units + 255) / 256 : 1048576);
         hipLaunchKernelGGL(vec4 ? splitk_reduce4_kernel : splitk_reduce_kernel, dim3(grid), dim3(256), 0,
                            stream, p.ws, C, (long long)ldc, (long long)strideC, (int)M, (int)N, (int)batch,
-                           p.splitK, alpha, beta);
+                           p.splitK, alpha, beta, bias);
         if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
     }
     return KS_OK;
@@ -404,6 +413,19 @@ extern "C" int ks_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_
     const int id = select_checked(KS_BF16, M, N, K, batch, transA, transB);
     if (id < 0) return id;
     return run(KS_BF16, id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_gemm_bias(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                            int64_t K, float alpha, const void *A, int64_t lda, const void *B,
+                            int64_t ldb, float beta, float *C, int64_t ldc, const float *bias,
+                            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                            void *stream) {
+    if (dtype != KS_F32 && dtype != KS_BF16) return KS_ERR_INVALID_ARG;
+    if (kernel_id < 0) {
+        kernel_id = select_checked(dtype, M, N, K, batch, transA, transB);
+        if (kernel_id < 0) return kernel_id;
+    }
+    return run(dtype, kernel_id, KS_GEMM_PASS, bias);
 }
 
 extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,

@@ -14,6 +14,7 @@ struct GemmParams {
     const void *B;
     float *C;
     float *ws;                       // split-K partial sums: [split][batch][M][N], dense
+    const float *bias;               // N values added to every row of C after alpha / beta, or null
     long long lda, ldb, ldc;
     long long strideA, strideB, strideC;
     int M, N, K, batch;
@@ -53,7 +54,9 @@ __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
 // outside the element loops so the per-element code is a bounds test and one store:
 //   SPLIT (a split-K instantiation): raw partial sum to this split's slice of the workspace;
 //   beta == 0: C = alpha * acc (C is never read);
-//   otherwise: C = alpha * acc + beta * C.
+//   otherwise: C = alpha * acc + beta * C;
+//   with a bias vector, bias[col] is added last (a split-K instantiation leaves that to the
+//   reduction pass).
 template <bool SPLIT, class Visit>
 __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord &tc, float *Cb,
                                            Visit visit) {
@@ -62,6 +65,18 @@ __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord 
         float *w = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)M * N;
         visit([&](int row, int col, float acc) {
             if (row < M && col < N) w[(long long)row * N + col] = acc;
+        });
+    } else if (p.bias != nullptr) {
+        const float alpha = p.alpha, beta = p.beta;
+        const float *bias = p.bias;
+        const long long ldc = p.ldc;
+        visit([&](int row, int col, float acc) {
+            if (row < M && col < N) {
+                float *c = Cb + (long long)row * ldc + col;
+                float v = alpha * acc;
+                if (beta != 0.0f) v = fmaf(beta, *c, v);
+                *c = v + bias[col];
+            }
         });
     } else if (p.beta == 0.0f) {
         const float alpha = p.alpha;
@@ -85,6 +100,7 @@ __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord 
 // instantiation, this partition's slice of the workspace (raw partial sums, dense rows of N).
 struct OutTarget {
     float *base;
+    const float *bias;               // added after alpha / beta; null in split-K instantiations
     long long ld;
     float alpha, beta;
     int M, N;
@@ -96,9 +112,9 @@ __device__ __forceinline__ OutTarget out_target(const GemmParams &p, const TileC
     o.M = p.M; o.N = p.N;
     if constexpr (SPLIT) {
         o.base = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)p.M * p.N;
-        o.ld = p.N; o.alpha = 1.0f; o.beta = 0.0f;
+        o.ld = p.N; o.alpha = 1.0f; o.beta = 0.0f; o.bias = nullptr;
     } else {
-        o.base = Cb; o.ld = p.ldc; o.alpha = p.alpha; o.beta = p.beta;
+        o.base = Cb; o.ld = p.ldc; o.alpha = p.alpha; o.beta = p.beta; o.bias = p.bias;
     }
     return o;
 }
@@ -111,7 +127,23 @@ template <bool SPLIT, int NE, class RowOff>
 __device__ __forceinline__ void store_lane_column(const OutTarget &o, int r0, int col, bool full,
                                                   const float (&v)[NE], RowOff rowOff) {
     float *ptr = o.base + (long long)r0 * o.ld + col;
-    if (full) {
+    if (!SPLIT && o.bias != nullptr) {
+        // bias form: the lane's column is fixed, so one bias value serves all its elements
+        if (col < o.N) {
+            const float bv = o.bias[col];
+            float old[NE];
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                old[e] = (o.beta != 0.0f && r0 + rowOff(e) < o.M) ? ptr[(long long)rowOff(e) * o.ld] : 0.0f;
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                if (r0 + rowOff(e) < o.M) {
+                    float x = o.alpha * v[e];
+                    if (o.beta != 0.0f) x = fmaf(o.beta, old[e], x);
+                    ptr[(long long)rowOff(e) * o.ld] = x + bv;
+                }
+        }
+    } else if (full) {
         if (SPLIT) {
 #pragma unroll
             for (int e = 0; e < NE; ++e) ptr[(long long)rowOff(e) * o.ld] = v[e];
