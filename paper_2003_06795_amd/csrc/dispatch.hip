@@ -7,6 +7,10 @@
 #include "../../include/ks_gemm.h"
 #include "registry.hpp"
 
+#ifndef KS_GRID3D_MAX
+#define KS_GRID3D_MAX 2048      // work-groups up to which the grid is launched three-dimensional
+#endif
+
 namespace ks {
 
 #define KS_DECL(n)                              \
@@ -242,6 +246,7 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
 
     const int64_t grid64 = (int64_t)p.tilesM * p.tilesN * batch * p.splitK;
     if (grid64 > 2147483647LL) return KS_ERR_UNSUPPORTED;
+    p.grid3d = grid64 <= KS_GRID3D_MAX && p.tilesM <= 65535 && batch * p.splitK <= 65535 ? 1 : 0;
 
     if (p.splitK > 1) {
         const size_t need = (size_t)p.splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);

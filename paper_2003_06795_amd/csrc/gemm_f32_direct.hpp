@@ -47,6 +47,24 @@ __device__ __forceinline__ floatx4 direct_fetch(const float *base, long long ld,
     return v;
 }
 
+// The same four values when the whole K-step is known to lie inside the K range: no predicate,
+// so nothing between the loads of a step makes the wave wait for an earlier one.  `lanePtr` is the
+// lane's element at k = 0 (KC: &op[idx][kLane]; otherwise &op[kLane][idx]); k is wave-uniform.
+template <bool KC, bool VEC>
+__device__ __forceinline__ floatx4 direct_fetch_full(const float *lanePtr, long long ld, int k) {
+    floatx4 v;
+    if constexpr (KC && VEC) {
+        v = *reinterpret_cast<const floatx4 *>(lanePtr + k);
+    } else if constexpr (KC) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = lanePtr[k + j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = lanePtr[(long long)(k + j) * ld];
+    }
+    return v;
+}
+
 template <int BM, int BN, int BK, int WM, int WN, bool SPLIT, bool AKC, bool BKC, bool VEC>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_f32_direct_kernel(const GemmParams p) {
     constexpr int FM = WM / 16, FN = WN / 16, NG = BK / 16;       // fragments per wave; k-groups per step
@@ -79,15 +97,37 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_f32_direct_ke
     constexpr int SET_REGS = 4 * NG * (FM + FN);
     constexpr int S = KS_F32_DIRECT_SETS(SET_REGS);
     floatx4 a[S][NG][FM], b[S][NG][FN];
+    // the lane's element at k = 0 of each fragment row / column, computed once
+    const float *aLane[FM], *bLane[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+        aLane[i] = AKC ? Ab + (long long)rowIdx[i] * p.lda + kLane : Ab + (long long)kLane * p.lda + rowIdx[i];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+        bLane[j] = BKC ? Bb + (long long)colIdx[j] * p.ldb + kLane : Bb + (long long)kLane * p.ldb + colIdx[j];
+    // A K-step wholly inside the range (all lanes agree) is fetched without predicates; only the
+    // step that the range cuts tests every element.
     auto fetch = [&](int set, int k0) {
+        if (k0 + BK <= kEnd) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
+            for (int g = 0; g < NG; ++g) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-                a[set][g][i] = direct_fetch<AKC, VEC>(Ab, p.lda, rowIdx[i], k0 + g * 16 + kLane, kEnd);
+                for (int i = 0; i < FM; ++i)
+                    a[set][g][i] = direct_fetch_full<AKC, VEC>(aLane[i], p.lda, k0 + g * 16);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                b[set][g][j] = direct_fetch<BKC, VEC>(Bb, p.ldb, colIdx[j], k0 + g * 16 + kLane, kEnd);
+                for (int j = 0; j < FN; ++j)
+                    b[set][g][j] = direct_fetch_full<BKC, VEC>(bLane[j], p.ldb, k0 + g * 16);
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+                    a[set][g][i] = direct_fetch<AKC, VEC>(Ab, p.lda, rowIdx[i], k0 + g * 16 + kLane, kEnd);
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    b[set][g][j] = direct_fetch<BKC, VEC>(Bb, p.ldb, colIdx[j], k0 + g * 16 + kLane, kEnd);
+            }
         }
     };
     auto mfmas = [&](int set) {

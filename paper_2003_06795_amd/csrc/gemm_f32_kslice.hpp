@@ -54,15 +54,37 @@ __global__ __launch_bounds__(64 * KW * (BM / W) * (BN / W)) void gemm_f32_kslice
     constexpr int SET_REGS = 4 * NG * (FM + FN);
     constexpr int S = KS_F32_DIRECT_SETS(SET_REGS);
     floatx4 a[S][NG][FM], b[S][NG][FN];
+    // the lane's element at k = 0 of each fragment row / column, computed once
+    const float *aLane[FM], *bLane[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+        aLane[i] = AKC ? Ab + (long long)rowIdx[i] * p.lda + kLane : Ab + (long long)kLane * p.lda + rowIdx[i];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+        bLane[j] = BKC ? Bb + (long long)colIdx[j] * p.ldb + kLane : Bb + (long long)kLane * p.ldb + colIdx[j];
+    // A K-step wholly inside the range (all lanes agree) is fetched without predicates; only the
+    // step that the range cuts tests every element.
     auto fetch = [&](int set, int k0) {
+        if (k0 + BK <= kEnd) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
+            for (int g = 0; g < NG; ++g) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-                a[set][g][i] = direct_fetch<AKC, VEC>(Ab, p.lda, rowIdx[i], k0 + g * 16 + kLane, kEnd);
+                for (int i = 0; i < FM; ++i)
+                    a[set][g][i] = direct_fetch_full<AKC, VEC>(aLane[i], p.lda, k0 + g * 16);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                b[set][g][j] = direct_fetch<BKC, VEC>(Bb, p.ldb, colIdx[j], k0 + g * 16 + kLane, kEnd);
+                for (int j = 0; j < FN; ++j)
+                    b[set][g][j] = direct_fetch_full<BKC, VEC>(bLane[j], p.ldb, k0 + g * 16);
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+                    a[set][g][i] = direct_fetch<AKC, VEC>(Ab, p.lda, rowIdx[i], k0 + g * 16 + kLane, kEnd);
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    b[set][g][j] = direct_fetch<BKC, VEC>(Bb, p.ldb, colIdx[j], k0 + g * 16 + kLane, kEnd);
+            }
         }
     };
     auto mfmas = [&](int set) {

@@ -13,7 +13,7 @@ namespace ks {
 template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT>
 static void launch_bf16_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
-    const dim3 g((unsigned)grid), b(NT);
+    const dim3 g = launch_grid(p, grid), b(NT);
 #define KS_V(A, B, V) hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, SPLIT, A, B, V>), g, b, 0, s, p)
     switch (variant) {
         case 0: KS_V(false, false, false); break;

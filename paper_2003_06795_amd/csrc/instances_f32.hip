@@ -16,7 +16,7 @@ namespace ks {
 template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT>
 static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads;
-    const dim3 g((unsigned)grid), b(NT);
+    const dim3 g = launch_grid(p, grid), b(NT);
 #define KS_V(A, B, V)                                                                                   \
     do {                                                                                                \
         if constexpr (CORE == CORE_KSLICE)                                                              \

@@ -20,8 +20,15 @@ struct GemmParams {
     int M, N, K, batch;
     int tilesM, tilesN;
     int splitK, kChunk;              // K range of split s is [s*kChunk, min(K, (s+1)*kChunk))
+    int grid3d;                      // 1: launched as (tilesN, tilesM, batch*splitK) work-groups
     float alpha, beta;
 };
+
+// launch shape that tile_of_block expects
+inline dim3 launch_grid(const GemmParams &p, int grid) {
+    return p.grid3d ? dim3((unsigned)p.tilesN, (unsigned)p.tilesM, (unsigned)(p.batch * p.splitK))
+                    : dim3((unsigned)grid);
+}
 
 struct TileCoord {
     int batch, split, tm, tn;
@@ -31,7 +38,22 @@ struct TileCoord {
 // Renumber so that each XCD owns one contiguous run of logical tile ids, then walk tiles in
 // bands of 8 tile-rows (column-major inside a band) so the tiles resident on one XCD form a
 // compact block that shares A row-panels and B column-panels in that XCD's L2.
+// Small grids (where a handful of integer divisions is a visible part of a 3 us kernel and L2
+// locality is not at stake) are launched three-dimensional instead and read their tile directly.
 __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
+    if (p.grid3d) {
+        TileCoord c;
+        c.tn = (int)blockIdx.x;
+        c.tm = (int)blockIdx.y;
+        const unsigned unit = blockIdx.z;
+        if (p.splitK == 1) {
+            c.batch = (int)unit; c.split = 0;
+        } else {
+            c.batch = (int)(unit / (unsigned)p.splitK);
+            c.split = (int)(unit - (unsigned)c.batch * (unsigned)p.splitK);
+        }
+        return c;
+    }
     const unsigned total = gridDim.x, id = blockIdx.x;
     const unsigned q = total >> 3, r = total & 7u, x = id & 7u;
     const unsigned logical = x * q + (x < r ? x : r) + (id >> 3);
