@@ -10,6 +10,9 @@
 #ifndef KS_GRID3D_MAX
 #define KS_GRID3D_MAX 2048      // work-groups up to which the grid is launched three-dimensional
 #endif
+#ifndef KS_GRID3D_BYTES
+#define KS_GRID3D_BYTES (4 << 20)   // ... and bytes of A and B together
+#endif
 
 namespace ks {
 
@@ -246,7 +249,13 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
 
     const int64_t grid64 = (int64_t)p.tilesM * p.tilesN * batch * p.splitK;
     if (grid64 > 2147483647LL) return KS_ERR_UNSUPPORTED;
-    p.grid3d = grid64 <= KS_GRID3D_MAX && p.tilesM <= 65535 && batch * p.splitK <= 65535 ? 1 : 0;
+    // three-dimensional launch only where the tile order cannot matter for L2: few work-groups
+    // and operands that fit one XCD's L2 several times over
+    const int64_t operandBytes = (M + N) * K * batch * (dtype == KS_F32 ? 4 : 2);
+    p.grid3d = grid64 <= KS_GRID3D_MAX && operandBytes <= KS_GRID3D_BYTES && p.tilesM <= 65535 &&
+                       batch * p.splitK <= 65535
+                   ? 1
+                   : 0;
 
     if (p.splitK > 1) {
         const size_t need = (size_t)p.splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
