@@ -31,11 +31,13 @@ def lib():
             f = getattr(L, name)
             f.argtypes = head
             f.restype = ctypes.c_int
-        for name in ("oracle_gemm_bias_f32", "oracle_gemm_bias_bf16"):
+        for name in ("oracle_gemm_bias_f32", "oracle_gemm_bias_bf16", "oracle_gemm_bias_f16"):
             f = getattr(L, name)
             f.argtypes = head + [_ptr]
             f.restype = ctypes.c_int
-        for name in ("oracle_gemm_f32_entries", "oracle_gemm_bf16_entries"):
+        L.oracle_widen_f16.argtypes = [ctypes.c_uint16]
+        L.oracle_widen_f16.restype = ctypes.c_double
+        for name in ("oracle_gemm_f32_entries", "oracle_gemm_bf16_entries", "oracle_gemm_f16_entries"):
             f = getattr(L, name)
             f.argtypes = head + [_i64, _ptr, _ptr, _ptr, _ptr]
             f.restype = ctypes.c_int
@@ -64,11 +66,14 @@ def _check_in(a, dtype):
 
 def gemm(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
          batch=1, strideA=0, strideB=0, strideC=0):
-    """In-place on C (float32 numpy buffer).  dtype is 'f32' or 'bf16' (A, B uint16 bits)."""
+    """In-place on C (float32 numpy buffer).  dtype is 'f32', 'bf16' or 'f16' (A, B uint16 bits)."""
     in_t = np.float32 if dtype == "f32" else np.uint16
     _check_in(A, in_t)
     _check_in(B, in_t)
     _check_in(C, np.float32)
+    if dtype == "f16":
+        return gemm_bias(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, None,
+                         batch, strideA, strideB, strideC)
     fn = lib().oracle_gemm_f32 if dtype == "f32" else lib().oracle_gemm_bf16
     rc = fn(int(transA), int(transB), M, N, K, alpha, _p(A), lda, _p(B), ldb, beta, _p(C), ldc,
             batch, strideA, strideB, strideC)
@@ -89,7 +94,8 @@ def gemm_bias(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ld
         _check_in(bias, np.float32)
         if bias.size < N:
             raise ValueError("bias shorter than N")
-    fn = lib().oracle_gemm_bias_f32 if dtype == "f32" else lib().oracle_gemm_bias_bf16
+    fn = {"f32": lib().oracle_gemm_bias_f32, "bf16": lib().oracle_gemm_bias_bf16,
+          "f16": lib().oracle_gemm_bias_f16}[dtype]
     rc = fn(int(transA), int(transB), M, N, K, alpha, _p(A), lda, _p(B), ldb, beta, _p(C), ldc,
             batch, strideA, strideB, strideC, _p(bias))
     if rc != 0:
@@ -109,9 +115,15 @@ def gemm_entries(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0
     ii = np.ascontiguousarray(ii, dtype=np.int64)
     jj = np.ascontiguousarray(jj, dtype=np.int64)
     out = np.empty(bb.shape[0], dtype=np.float32)
-    fn = lib().oracle_gemm_f32_entries if dtype == "f32" else lib().oracle_gemm_bf16_entries
+    fn = {"f32": lib().oracle_gemm_f32_entries, "bf16": lib().oracle_gemm_bf16_entries,
+          "f16": lib().oracle_gemm_f16_entries}[dtype]
     rc = fn(int(transA), int(transB), M, N, K, alpha, _p(A), lda, _p(B), ldb, beta, _p(C0), ldc,
             batch, strideA, strideB, strideC, bb.shape[0], _p(bb), _p(ii), _p(jj), _p(out))
     if rc != 0:
         raise ValueError("oracle gemm_entries: invalid arguments")
     return out
+
+
+def widen_f16(bits):
+    """The oracle's own binary16 -> float64 conversion of one bit pattern."""
+    return lib().oracle_widen_f16(int(bits))

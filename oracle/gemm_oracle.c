@@ -22,6 +22,8 @@
  *   - beta == 0 means C is not read (NaN/Inf already in C do not propagate).
  *   - alpha == 0 gets no special case: 0 * acc is computed.
  *   - bf16 operands are widened exactly (bf16 is the top 16 bits of an fp32).
+ *   - fp16 operands (IEEE 754 binary16: 1 sign, 5 exponent, 10 fraction bits,
+ *     bias 15, subnormals, infinities and NaNs) are widened exactly as well.
  *   - the fp64 value alpha*acc + beta*c0 is rounded once to fp32 on store.
  *   - the *_bias entry points add a length-N fp32 vector to every row of every
  *     batch item, out[b][i][j] = alpha*acc + beta*c0 + bias[j]: the bias of a
@@ -34,6 +36,7 @@
 #include <stddef.h>
 #include <stdint.h>
 #include <string.h>
+#include <math.h>
 
 static inline double widen_f32(const void *p, int64_t idx) {
     return (double)((const float *)p)[idx];
@@ -44,6 +47,22 @@ static inline double widen_bf16(const void *p, int64_t idx) {
     float f;
     memcpy(&f, &bits, sizeof f);
     return (double)f;
+}
+
+/* binary16 -> double from the bit fields: (-1)^s * 2^(e-15) * (1 + f/1024) for 0 < e < 31,
+ * (-1)^s * 2^-14 * (f/1024) for e == 0, infinity / NaN for e == 31 */
+static inline double widen_f16(const void *p, int64_t idx) {
+    uint16_t h = ((const uint16_t *)p)[idx];
+    int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 31) {
+        v = f ? (double)NAN : (double)INFINITY;
+    } else if (e == 0) {
+        v = ldexp((double)f, -24);
+    } else {
+        v = ldexp((double)(1024 + f), e - 25);
+    }
+    return sign ? -v : v;
 }
 
 typedef double (*widen_fn)(const void *, int64_t);
@@ -127,6 +146,17 @@ int oracle_gemm_bias_bf16(int transA, int transB, int64_t M, int64_t N, int64_t 
                     batch, strideA, strideB, strideC, bias);
 }
 
+int oracle_gemm_bias_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                         float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                         float beta, float *C, int64_t ldc, int64_t batch,
+                         int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
+    return gemm_any(widen_f16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                    batch, strideA, strideB, strideC, bias);
+}
+
+/* one fp16 bit pattern widened, for the pins of the conversion itself */
+double oracle_widen_f16(uint16_t bits) { return widen_f16(&bits, 0); }
+
 /*
  * The same definition for a list of n output entries (b[t], i[t], j[t]) only:
  * out[t] = (float)(alpha * dot + beta * C0[b,i,j]).  C0 is the output buffer
@@ -172,6 +202,16 @@ int oracle_gemm_bf16_entries(int transA, int transB, int64_t M, int64_t N, int64
                              int64_t n, const int64_t *bb, const int64_t *ii, const int64_t *jj,
                              float *out) {
     return entries_any(widen_bf16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc,
+                       batch, strideA, strideB, strideC, n, bb, ii, jj, out);
+}
+
+int oracle_gemm_f16_entries(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                            float alpha, const uint16_t *A, int64_t lda, const uint16_t *B,
+                            int64_t ldb, float beta, const float *C0, int64_t ldc, int64_t batch,
+                            int64_t strideA, int64_t strideB, int64_t strideC,
+                            int64_t n, const int64_t *bb, const int64_t *ii, const int64_t *jj,
+                            float *out) {
+    return entries_any(widen_f16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0, ldc,
                        batch, strideA, strideB, strideC, n, bb, ii, jj, out);
 }
 

@@ -6,8 +6,8 @@ import workloads as wl
 
 def operand_matrices(p):
     """Lists (per batch item) of op(A) [M x K], op(B) [K x N] as float64 and C0 [M x N] float32 views."""
-    a = p.A if p.dtype == "f32" else wl.bf16_to_f32(p.A)
-    b = p.B if p.dtype == "f32" else wl.bf16_to_f32(p.B)
+    a = wl.operand_as_f32(p.dtype, p.A)
+    b = wl.operand_as_f32(p.dtype, p.B)
     As, Bs, Cs = [], [], []
     for t in range(p.batch):
         ra, ca = (p.K, p.M) if p.transA else (p.M, p.K)

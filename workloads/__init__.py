@@ -17,7 +17,7 @@ import numpy as np
 
 __all__ = [
     "Problem", "make_problem", "uniform_pm1", "normal_scaled", "f32_to_bf16_rne",
-    "bf16_to_f32", "config1_problem", "CONFIG1_TILES", "config2_shapes", "config2_split",
+    "bf16_to_f32", "f32_to_f16_bits", "f16_bits_to_f32", "operand_as_f32", "config1_problem", "CONFIG1_TILES", "config2_shapes", "config2_split",
     "config2_rows", "config2_extra_rows", "config3_shapes", "config4_shapes", "config5_shapes", "bf16_tuning_shapes",
     "bf16_tuning_split",
 ]
@@ -57,6 +57,23 @@ def f32_to_bf16_rne(x):
     return r.astype(np.uint16)
 
 
+def f32_to_f16_bits(x):
+    """float32 -> IEEE binary16 bit patterns (uint16), round to nearest even (numpy's conversion)."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b):
+    """binary16 bit patterns -> float32 (exact)."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def operand_as_f32(dtype, buf):
+    """The operand buffer of a Problem as float32 values, whatever its storage type."""
+    if dtype == "f32":
+        return buf
+    return bf16_to_f32(buf) if dtype == "bf16" else f16_bits_to_f32(buf)
+
+
 def bf16_to_f32(b):
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
@@ -66,7 +83,7 @@ def bf16_to_f32(b):
 @dataclass
 class Problem:
     """One GEMM call, in the argument order of the C ABI, with host buffers."""
-    dtype: str                    # 'f32' | 'bf16'
+    dtype: str                    # 'f32' | 'bf16' | 'f16'
     transA: int
     transB: int
     M: int
@@ -92,8 +109,8 @@ class Problem:
 
     def max_abs(self):
         """(max|A|, max|B|, max|C0|) over the logical entries' buffers, as float."""
-        a = self.A if self.dtype == "f32" else bf16_to_f32(self.A)
-        b = self.B if self.dtype == "f32" else bf16_to_f32(self.B)
+        a = operand_as_f32(self.dtype, self.A)
+        b = operand_as_f32(self.dtype, self.B)
         f = lambda v: float(np.max(np.abs(v))) if v.size else 0.0
         c = self.C0[np.isfinite(self.C0)]
         return f(a), f(b), f(c)
@@ -134,6 +151,8 @@ def make_problem(dtype, transA, transB, M, N, K, batch=1, alpha=1.0, beta=0.0, s
     A, B = draw(nA, 0), draw(nB, 1)
     if dtype == "bf16":
         A, B = f32_to_bf16_rne(A), f32_to_bf16_rne(B)
+    elif dtype == "f16":
+        A, B = f32_to_f16_bits(A), f32_to_f16_bits(B)
     if c_fill == "uniform":
         C0 = uniform_pm1(nC, seed, key, 2)
     elif c_fill == "nan":
