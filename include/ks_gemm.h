@@ -47,7 +47,9 @@ typedef enum {
     KS_ERR_WORKSPACE = -4      /* a split-K kernel needs a larger registered workspace */
 } ks_status;
 
-typedef enum { KS_F32 = 0, KS_BF16 = 1 } ks_dtype;           /* type of A and B; C is fp32 */
+/* type of A and B; C is fp32.  KS_F16 (IEEE binary16) runs the instantiations of the 16-bit family
+ * (the ids, registry entries and deployed tree of KS_BF16) with the binary16 MFMA instructions. */
+typedef enum { KS_F32 = 0, KS_BF16 = 1, KS_F16 = 2 } ks_dtype;
 typedef enum {
     KS_CORE_FMA = 0, KS_CORE_MFMA16 = 1, KS_CORE_MFMA32 = 2, KS_CORE_DIRECT = 3, KS_CORE_KSLICE = 4
 } ks_core;
@@ -107,6 +109,20 @@ int ks_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
                  float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
                  float beta, float *C, int64_t ldc,
                  int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+
+/* fp16 inputs (one of the data types the paper's Section II kernel can be instantiated for is
+ * left open; this is the IEEE binary16 form): A and B are binary16 bit patterns, products are
+ * exact in fp32 and accumulate in fp32 like the bf16 form.  Arguments, statuses and ownership as
+ * for ks_gemm_bf16; kernel ids are those of KS_BF16. */
+int ks_gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                float beta, float *C, int64_t ldc,
+                int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+int ks_gemm_f16_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                            float alpha, const uint16_t *A, int64_t lda, const uint16_t *B,
+                            int64_t ldb, float beta, float *C, int64_t ldc,
+                            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                            void *stream);
 
 /* Tuner path (Section II-A brute force): the same call with the instantiation forced. */
 int ks_gemm_f32_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,

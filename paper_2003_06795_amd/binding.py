@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libks_gemm.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 0, -1, -2, -3, -4
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 CORE_NAMES = {0: "fma", 1: "mfma16", 2: "mfma32", 3: "direct", 4: "kslice"}
 NUM_RAW_FEATURES, NUM_FEATURES, MAX_TREE_NODES = 6, 10, 4096
 FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "min(M,N)", "max(M,N)"]
@@ -53,7 +53,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
-    "ks_gemm_bias", "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
+    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
@@ -77,6 +77,8 @@ def lib():
     L = ctypes.CDLL(LIB_PATH)
     L.ks_gemm_f32.argtypes = _GEMM
     L.ks_gemm_bf16.argtypes = _GEMM
+    L.ks_gemm_f16.argtypes = _GEMM
+    L.ks_gemm_f16_with_kernel.argtypes = [_i] + _GEMM
     L.ks_gemm_f32_with_kernel.argtypes = [_i] + _GEMM
     L.ks_gemm_bf16_with_kernel.argtypes = [_i] + _GEMM
     L.ks_gemm_bias.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
@@ -155,6 +157,19 @@ def gemm_bf16(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batc
               strideB=0, strideC=0, stream=None):
     _check(lib().ks_gemm_bf16(*_gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
                                           batch, strideA, strideB, strideC, stream)), "ks_gemm_bf16")
+
+
+def gemm_f16(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batch=1, strideA=0,
+             strideB=0, strideC=0, stream=None):
+    _check(lib().ks_gemm_f16(*_gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                                         batch, strideA, strideB, strideC, stream)), "ks_gemm_f16")
+
+
+def gemm_f16_with_kernel(kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                         batch=1, strideA=0, strideB=0, strideC=0, stream=None):
+    _check(lib().ks_gemm_f16_with_kernel(
+        int(kernel_id), *_gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                                    batch, strideA, strideB, strideC, stream)), "ks_gemm_f16_with_kernel")
 
 
 def gemm_f32_with_kernel(kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,

@@ -110,7 +110,7 @@ int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles) {
 
 const InstanceDesc *desc_of(int dtype, int id) {
     if (dtype == KS_F32) return (id >= 0 && id < kNumF32) ? &kF32[id] : nullptr;
-    if (dtype == KS_BF16) return (id >= 0 && id < kNumBf16) ? &kBf16[id] : nullptr;
+    if (dtype == KS_BF16 || dtype == KS_F16) return (id >= 0 && id < kNumBf16) ? &kBf16[id] : nullptr;
     return nullptr;
 }
 
@@ -275,12 +275,13 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
 
     // bf16 fast path: operand tiles go global -> LDS directly.  Needs 16-byte accesses, whole
     // K-steps, and tile-relative byte offsets that fit 32 bits.
-    const bool dma = dtype == KS_BF16 && vec && g_forceGeneric == 0 && K % d->bk == 0 &&
+    const int f16Bit = dtype == KS_F16 ? 16 : 0;     // same 16-bit members, binary16 MFMA
+    const bool dma = dtype != KS_F32 && vec && g_forceGeneric == 0 && K % d->bk == 0 &&
                      lda <= (1LL << 22) && ldb <= (1LL << 22);
     if (dma)
-        g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0) + splitBit, stream);
+        g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0) + splitBit + f16Bit, stream);
     else
-        (dtype == KS_F32 ? g_f32[id] : g_bf16[id])(p, (int)grid64, variant, stream);
+        (dtype == KS_F32 ? g_f32[id] : g_bf16[id])(p, (int)grid64, variant + f16Bit, stream);
     if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
 
     if (p.splitK > 1) {
@@ -304,7 +305,7 @@ using namespace ks;
 
 extern "C" int ks_num_kernels(int dtype) {
     if (dtype == KS_F32) return kNumF32;
-    if (dtype == KS_BF16) return kNumBf16;
+    if (dtype == KS_BF16 || dtype == KS_F16) return kNumBf16;
     return KS_ERR_INVALID_ARG;
 }
 
@@ -429,12 +430,29 @@ extern "C" int ks_gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_
     return run(KS_BF16, id, KS_GEMM_PASS);
 }
 
+extern "C" int ks_gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+                           const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, float beta,
+                           float *C, int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,
+                           int64_t strideC, void *stream) {
+    const int id = select_checked(KS_F16, M, N, K, batch, transA, transB);
+    if (id < 0) return id;
+    return run(KS_F16, id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_gemm_f16_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                                       int64_t K, float alpha, const uint16_t *A, int64_t lda,
+                                       const uint16_t *B, int64_t ldb, float beta, float *C,
+                                       int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,
+                                       int64_t strideC, void *stream) {
+    return run(KS_F16, kernel_id, KS_GEMM_PASS);
+}
+
 extern "C" int ks_gemm_bias(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
                             int64_t K, float alpha, const void *A, int64_t lda, const void *B,
                             int64_t ldb, float beta, float *C, int64_t ldc, const float *bias,
                             int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
                             void *stream) {
-    if (dtype != KS_F32 && dtype != KS_BF16) return KS_ERR_INVALID_ARG;
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
     if (kernel_id < 0) {
         kernel_id = select_checked(dtype, M, N, K, batch, transA, transB);
         if (kernel_id < 0) return kernel_id;
@@ -447,7 +465,7 @@ extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, in
                             int64_t ldb, float beta, float *C, int64_t ldc, int64_t batch,
                             int64_t strideA, int64_t strideB, int64_t strideC, void *stream,
                             int warmup, int iters, int reps, float *ms_out) {
-    if (dtype != KS_F32 && dtype != KS_BF16) return KS_ERR_INVALID_ARG;
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
     if (iters < 1 || iters > 1024 || reps < 1 || warmup < 0 || !ms_out) return KS_ERR_INVALID_ARG;
     if (kernel_id < 0) {
         kernel_id = select_checked(dtype, M, N, K, batch, transA, transB);

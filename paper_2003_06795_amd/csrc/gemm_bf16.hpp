@@ -18,7 +18,25 @@
 namespace ks {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// The 16-bit members move bit patterns; only the MFMA instruction knows whether they are bf16 or
+// IEEE binary16 (F16: v_mfma_f32_16x16x32_f16 / v_mfma_f32_32x32x16_f16).
+template <bool F16>
+__device__ __forceinline__ floatx4 mfma_16x16x32(bf16x8 a, bf16x8 b, floatx4 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+template <bool F16>
+__device__ __forceinline__ floatx16 mfma_32x32x16(bf16x8 a, bf16x8 b, floatx16 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
 
 template <int BK>
 struct Bf16Lds {
@@ -119,7 +137,8 @@ struct Bf16TileLoader {
     }
 };
 
-template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT, bool AKC, bool BKC, bool VEC>
+template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT, bool AKC, bool BKC, bool VEC,
+          bool F16 = false>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_kernel(const GemmParams p) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     constexpr int FM = WM / F, FN = WN / F;
@@ -188,9 +207,9 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_kernel(c
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     if constexpr (F == 16)
-                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc16[i][j], 0, 0, 0);
+                        acc16[i][j] = mfma_16x16x32<F16>(a[i], b[j], acc16[i][j]);
                     else
-                        acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc32[i][j], 0, 0, 0);
+                        acc32[i][j] = mfma_32x32x16<F16>(a[i], b[j], acc32[i][j]);
                 }
         }
         if (more) {

@@ -134,7 +134,8 @@ struct InterleaveHint {
     }
 };
 
-template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT, bool AKC, bool BKC>
+template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT, bool AKC, bool BKC,
+          bool F16 = false>
 __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kernel(const GemmParams p) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int FM = WM / F, FN = WN / F;
@@ -215,9 +216,9 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     if constexpr (F == 16)
-                        acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[cur][i], b[cur][j], acc16[i][j], 0, 0, 0);
+                        acc16[i][j] = mfma_16x16x32<F16>(a[cur][i], b[cur][j], acc16[i][j]);
                     else
-                        acc32[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc32[i][j], 0, 0, 0);
+                        acc32[i][j] = mfma_32x32x16<F16>(a[cur][i], b[cur][j], acc32[i][j]);
                 }
             if (sub + 1 < NSUB) InterleaveHint<0, NMFMA, NREAD>::emit();
             else InterleaveHint<0, NMFMA, 0>::emit();

@@ -14,8 +14,15 @@ template <int F, int BM, int BN, int BK, int WM, int WN, bool SPLIT>
 static void launch_bf16_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     const dim3 g = launch_grid(p, grid), b(NT);
-#define KS_V(A, B, V) hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, SPLIT, A, B, V>), g, b, 0, s, p)
-    switch (variant) {
+    // variant bit 4: the operands are IEEE binary16 instead of bf16
+#define KS_V(A, B, V)                                                                                        \
+    do {                                                                                                     \
+        if (variant & 16)                                                                                    \
+            hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, SPLIT, A, B, V, true>), g, b, 0, s, p);  \
+        else                                                                                                 \
+            hipLaunchKernelGGL((gemm_bf16_kernel<F, BM, BN, BK, WM, WN, SPLIT, A, B, V, false>), g, b, 0, s, p); \
+    } while (0)
+    switch (variant & 7) {
         case 0: KS_V(false, false, false); break;
         case 1: KS_V(false, false, true); break;
         case 2: KS_V(false, true, false); break;
@@ -32,10 +39,10 @@ static void launch_bf16_fixed(const GemmParams &p, int grid, int variant, hipStr
 template <int F, int BM, int BN, int BK, int WM, int WN, int SPLITMODE>
 static void launch_bf16(const GemmParams &p, int grid, int variant, hipStream_t s) {
     if constexpr (SPLITMODE == 2) {
-        if (variant & 8) launch_bf16_fixed<F, BM, BN, BK, WM, WN, true>(p, grid, variant & 7, s);
-        else launch_bf16_fixed<F, BM, BN, BK, WM, WN, false>(p, grid, variant & 7, s);
+        if (variant & 8) launch_bf16_fixed<F, BM, BN, BK, WM, WN, true>(p, grid, variant & 23, s);
+        else launch_bf16_fixed<F, BM, BN, BK, WM, WN, false>(p, grid, variant & 23, s);
     } else {
-        launch_bf16_fixed<F, BM, BN, BK, WM, WN, SPLITMODE == 1>(p, grid, variant & 7, s);
+        launch_bf16_fixed<F, BM, BN, BK, WM, WN, SPLITMODE == 1>(p, grid, variant & 23, s);
     }
 }
 

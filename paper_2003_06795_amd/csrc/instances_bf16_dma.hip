@@ -15,8 +15,15 @@ template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT>
 static void launch_bf16_dma_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = 64 * (BM / WM) * (BN / WN);
     const dim3 g = launch_grid(p, grid), b(NT);
-#define KS_V(A, B) hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B>), g, b, 0, s, p)
-    switch (variant) {
+    // variant bit 4: the operands are IEEE binary16 instead of bf16
+#define KS_V(A, B)                                                                                                  \
+    do {                                                                                                            \
+        if (variant & 16)                                                                                           \
+            hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B, true>), g, b, 0, s, p);  \
+        else                                                                                                        \
+            hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B, false>), g, b, 0, s, p); \
+    } while (0)
+    switch (variant & 3) {
         case 0: KS_V(false, false); break;
         case 1: KS_V(false, true); break;
         case 2: KS_V(true, false); break;
@@ -29,10 +36,10 @@ static void launch_bf16_dma_fixed(const GemmParams &p, int grid, int variant, hi
 template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, int SPLITMODE>
 static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStream_t s) {
     if constexpr (SPLITMODE == 2) {
-        if (variant & 8) launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, true>(p, grid, variant & 3, s);
-        else launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, false>(p, grid, variant & 3, s);
+        if (variant & 8) launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, true>(p, grid, variant & 19, s);
+        else launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, false>(p, grid, variant & 19, s);
     } else {
-        launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, SPLITMODE == 1>(p, grid, variant & 3, s);
+        launch_bf16_dma_fixed<F, BM, BN, BK, WM, WN, STAGES, SPLITMODE == 1>(p, grid, variant & 19, s);
     }
 }
 

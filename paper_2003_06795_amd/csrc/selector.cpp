@@ -61,6 +61,7 @@ extern "C" int ks_features(int64_t M, int64_t N, int64_t K, int64_t batch, int t
 
 extern "C" int ks_select(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int transA,
                          int transB) {
+    if (dtype == KS_F16) dtype = KS_BF16;          // the fp16 form runs the 16-bit family with its tree
     if (dtype != KS_F32 && dtype != KS_BF16) return KS_ERR_INVALID_ARG;
     int64_t f[KS_NUM_FEATURES];
     const int rc = ks_features(M, N, K, batch, transA, transB, f);

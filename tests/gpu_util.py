@@ -6,7 +6,9 @@ import torch
 import paper_2003_06795_amd.binding as ks
 from oracle import gemm as og
 
-DT = {"f32": ks.F32, "bf16": ks.BF16}
+DT = {"f32": ks.F32, "bf16": ks.BF16, "f16": ks.F16}
+GEMM = {"f32": ks.gemm_f32, "bf16": ks.gemm_bf16, "f16": ks.gemm_f16}
+GEMM_K = {"f32": ks.gemm_f32_with_kernel, "bf16": ks.gemm_bf16_with_kernel, "f16": ks.gemm_f16_with_kernel}
 
 
 class DeviceProblem:
@@ -27,9 +29,9 @@ class DeviceProblem:
         args = (p.transA, p.transB, p.M, p.N, p.K, p.alpha, self.A, p.lda, self.B, p.ldb, p.beta, C,
                 p.ldc, p.batch, p.strideA, p.strideB, p.strideC)
         if kernel_id is None:
-            (ks.gemm_f32 if p.dtype == "f32" else ks.gemm_bf16)(*args)
+            GEMM[p.dtype](*args)
         else:
-            (ks.gemm_f32_with_kernel if p.dtype == "f32" else ks.gemm_bf16_with_kernel)(kernel_id, *args)
+            GEMM_K[p.dtype](kernel_id, *args)
         torch.cuda.synchronize()
         return C.cpu().numpy()[:p.C0.size]
 
