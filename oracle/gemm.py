@@ -35,6 +35,10 @@ def lib():
             f = getattr(L, name)
             f.argtypes = head + [_ptr]
             f.restype = ctypes.c_int
+        L.oracle_round_to_bf16.argtypes = [ctypes.c_double]
+        L.oracle_round_to_bf16.restype = ctypes.c_uint16
+        L.oracle_gemm_out_bf16.argtypes = [ctypes.c_int] + head + [_ptr]
+        L.oracle_gemm_out_bf16.restype = ctypes.c_int
         L.oracle_widen_f16.argtypes = [ctypes.c_uint16]
         L.oracle_widen_f16.restype = ctypes.c_double
         for name in ("oracle_gemm_f32_entries", "oracle_gemm_bf16_entries", "oracle_gemm_f16_entries"):
@@ -127,3 +131,28 @@ def gemm_entries(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C0
 def widen_f16(bits):
     """The oracle's own binary16 -> float64 conversion of one bit pattern."""
     return lib().oracle_widen_f16(int(bits))
+
+
+def round_to_bf16(x):
+    """The oracle's own float64 -> bf16 (bit pattern) rounding of one value."""
+    return lib().oracle_round_to_bf16(float(x))
+
+
+def gemm_out_bf16(dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C16, ldc, bias=None,
+                  batch=1, strideA=0, strideB=0, strideC=0):
+    """C kept in bf16 (uint16 bit patterns, in place): bf16(alpha*op(A)*op(B) + beta*C + bias[j]),
+    the sum formed in fp64 and rounded once to nearest even."""
+    in_t = np.float32 if dtype == "f32" else np.uint16
+    _check_in(A, in_t)
+    _check_in(B, in_t)
+    _check_in(C16, np.uint16)
+    if bias is not None:
+        _check_in(bias, np.float32)
+        if bias.size < N:
+            raise ValueError("bias shorter than N")
+    rc = lib().oracle_gemm_out_bf16({"f32": 0, "bf16": 1, "f16": 2}[dtype], int(transA), int(transB), M, N, K,
+                                    alpha, _p(A), lda, _p(B), ldb, beta, _p(C16), ldc, batch, strideA,
+                                    strideB, strideC, _p(bias))
+    if rc != 0:
+        raise ValueError("oracle gemm_out_bf16: invalid arguments")
+    return C16

@@ -25,6 +25,12 @@
  *   - fp16 operands (IEEE 754 binary16: 1 sign, 5 exponent, 10 fraction bits,
  *     bias 15, subnormals, infinities and NaNs) are widened exactly as well.
  *   - the fp64 value alpha*acc + beta*c0 is rounded once to fp32 on store.
+ *   - the *_out_bf16 entry points keep C in bf16: the old value (read only when
+ *     beta != 0) is widened exactly, and the fp64 value alpha*acc + beta*c0 + bias[j]
+ *     is rounded ONCE to bf16, to nearest with ties to even (8 significant bits,
+ *     fp32's exponent range, subnormals; overflow goes to infinity).  Mixed
+ *     precision of this kind is what Section II's remark that the kernel is
+ *     templated over its data type leaves open; the reading is ours.
  *   - the *_bias entry points add a length-N fp32 vector to every row of every
  *     batch item, out[b][i][j] = alpha*acc + beta*c0 + bias[j]: the bias of a
  *     fully-connected layer whose weights are op(B) (Section II-A lists
@@ -64,6 +70,29 @@ static inline double widen_f16(const void *p, int64_t idx) {
     }
     return sign ? -v : v;
 }
+
+/* double -> bf16 bit pattern, round to nearest even, by the format's definition */
+static uint16_t round_to_bf16(double x) {
+    uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    if (isnan(x)) return 0x7FC0u;
+    double a = fabs(x);
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                 /* a = m * 2^e, 0.5 <= m < 1  ->  floor(log2 a) = e - 1 */
+    int ex = e - 1;
+    if (ex < -126) ex = -126;           /* subnormal spacing */
+    double q = ldexp(1.0, ex - 7);      /* spacing of bf16 values in this binade */
+    double n = nearbyint(a / q);        /* default rounding mode: to nearest, ties to even */
+    double v = n * q;
+    if (v >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7F80u);
+    float f = (float)v;                 /* exact: v has at most 8 significant bits */
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    return (uint16_t)(sign | (bits >> 16));
+}
+
+uint16_t oracle_round_to_bf16(double x) { return round_to_bf16(x); }
 
 typedef double (*widen_fn)(const void *, int64_t);
 
@@ -152,6 +181,40 @@ int oracle_gemm_bias_f16(int transA, int transB, int64_t M, int64_t N, int64_t K
                          int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
     return gemm_any(widen_f16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
                     batch, strideA, strideB, strideC, bias);
+}
+
+/* C kept in bf16 (see the header): in place on C16 */
+static int gemm_out16_any(widen_fn w, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                          float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                          float beta, uint16_t *C16, int64_t ldc, int64_t batch,
+                          int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
+    if (check_args(transA, transB, M, N, K, lda, ldb, ldc, batch)) return -1;
+    if (M == 0 || N == 0 || batch == 0) return 0;
+    int64_t rows = batch * M;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        int64_t b = r / M, i = r % M;
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = dot_entry(w, transA, transB, K, A, b * strideA, lda,
+                                   B, b * strideB, ldb, i, j);
+            uint16_t *c = C16 + b * strideC + i * ldc + j;
+            double out = (double)alpha * acc;
+            if (beta != 0.0f) out += (double)beta * widen_bf16(c, 0);
+            if (bias) out += (double)bias[j];
+            *c = round_to_bf16(out);
+        }
+    }
+    return 0;
+}
+
+int oracle_gemm_out_bf16(int in_dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                         float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                         float beta, uint16_t *C16, int64_t ldc, int64_t batch,
+                         int64_t strideA, int64_t strideB, int64_t strideC, const float *bias) {
+    widen_fn w = in_dtype == 0 ? widen_f32 : in_dtype == 1 ? widen_bf16 : in_dtype == 2 ? widen_f16 : NULL;
+    if (!w) return -1;
+    return gemm_out16_any(w, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C16, ldc,
+                          batch, strideA, strideB, strideC, bias);
 }
 
 /* one fp16 bit pattern widened, for the pins of the conversion itself */
