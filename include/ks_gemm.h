@@ -148,6 +148,18 @@ int ks_gemm_bias(int dtype, int kernel_id, int transA, int transB, int64_t M, in
                  float beta, float *C, int64_t ldc, const float *bias,
                  int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
 
+/* Output kept in bf16 (mixed precision for inference-style layers; the accumulator stays fp32):
+ * C16 holds bf16 bit patterns, M x N with row stride ldc and batch stride strideC counted in
+ * 2-byte elements; when beta != 0 the old value is widened exactly, and
+ * alpha * acc + beta * C + bias[j] (fp32) is rounded to bf16, to nearest with ties to even, in the
+ * kernel's epilogue (split-K members: in the reduction pass; their partial sums stay fp32).
+ * bias may be NULL.  dtype: type of A and B (any ks_dtype); kernel_id < 0 selects.  Other
+ * arguments, statuses and ownership as for ks_gemm_bias. */
+int ks_gemm_out_bf16(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                     float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                     float beta, uint16_t *C16, int64_t ldc, const float *bias,
+                     int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+
 /* Brute-force timing of one (workload, instantiation) cell (Section II-A: runtime recorded over a
  * number of iterations).  Runs `warmup` untimed launches, then `iters` samples; a sample is
  * `reps` back-to-back launches bracketed by one pair of HIP events on `stream`.  Synchronises and

@@ -116,11 +116,15 @@ const InstanceDesc *desc_of(int dtype, int id) {
 
 // C = beta * C (+ bias) for K == 0 (C is not read when beta == 0)
 __global__ void scale_c_kernel(float *C, long long ldc, long long strideC, int M, int N, int batch,
-                               float beta, const float *bias) {
+                               float beta, const float *bias, int out16) {
     const long long total = (long long)batch * M * N;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
         const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
+        if (out16) {
+            store_bf16_out(C, b * strideC + (r / N) * ldc + (r % N), 0.0f, 0.0f, beta, bias ? bias[r % N] : 0.0f);
+            continue;
+        }
         float *c = C + b * strideC + (r / N) * ldc + (r % N);
         const float v = beta == 0.0f ? 0.0f : beta * *c;
         *c = bias ? v + bias[r % N] : v;
@@ -165,13 +169,17 @@ __global__ void splitk_reduce4_kernel(const float *ws, float *C, long long ldc, 
 // Split-K second pass: C = alpha * (ws[0] + ws[1] + ... in this fixed order) + beta * C (+ bias)
 __global__ void splitk_reduce_kernel(const float *ws, float *C, long long ldc, long long strideC, int M,
                                      int N, int batch, int splitK, float alpha, float beta,
-                                     const float *bias) {
+                                     const float *bias, int out16) {
     const long long per = (long long)batch * M * N;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < per;
          i += (long long)gridDim.x * blockDim.x) {
         float acc = ws[i];
         for (int s = 1; s < splitK; ++s) acc += ws[(long long)s * per + i];
         const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
+        if (out16) {
+            store_bf16_out(C, b * strideC + (r / N) * ldc + (r % N), acc, alpha, beta, bias ? bias[r % N] : 0.0f);
+            continue;
+        }
         float *c = C + b * strideC + (r / N) * ldc + (r % N);
         float v = alpha * acc;
         if (beta != 0.0f) v = fmaf(beta, *c, v);
@@ -206,7 +214,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
         const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
         int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
-        const float *bias = nullptr) {
+        const float *bias = nullptr, int out16 = 0) {
     const InstanceDesc *d = desc_of(dtype, id);
     if (!d) return KS_ERR_INVALID_ARG;
     const int rc = validate(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, batch, strideC);
@@ -221,14 +229,15 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
         const long long total = (long long)batch * M * N;
         const int grid = (int)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
         hipLaunchKernelGGL(scale_c_kernel, dim3(grid), dim3(256), 0, stream, C, (long long)ldc,
-                           (long long)strideC, (int)M, (int)N, (int)batch, beta, bias);
+                           (long long)strideC, (int)M, (int)N, (int)batch, beta, bias, out16);
         return hipGetLastError() == hipSuccess ? KS_OK : KS_ERR_LAUNCH;
     }
 
     GemmParams p;
-    p.A = A; p.B = B; p.C = C; p.ws = nullptr; p.bias = bias;
+    p.A = A; p.B = B; p.C = C; p.ws = nullptr; p.bias = bias; p.out16 = out16;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
-    p.strideA = strideA; p.strideB = strideB; p.strideC = strideC;
+    p.strideA = strideA; p.strideB = strideB;
+    p.strideC = out16 ? 0 : strideC; p.strideC16 = out16 ? strideC : 0;
     p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = (int)batch;
     p.tilesM = (int)((M + d->bm - 1) / d->bm);
     p.tilesN = (int)((N + d->bn - 1) / d->bn);
@@ -286,13 +295,17 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
 
     if (p.splitK > 1) {
         const long long total = (long long)batch * M * N;
-        const bool vec4 = N % 4 == 0 && ldc % 4 == 0 && aligned(C, 16) && aligned(p.ws, 16) &&
+        const bool vec4 = !out16 && N % 4 == 0 && ldc % 4 == 0 && aligned(C, 16) && aligned(p.ws, 16) &&
                           (batch == 1 || strideC % 4 == 0);
         const long long units = vec4 ? total / 4 : total;
         const int grid = (int)((units + 255) / 256 < 1048576 ? (units + 255) / 256 : 1048576);
-        hipLaunchKernelGGL(vec4 ? splitk_reduce4_kernel : splitk_reduce_kernel, dim3(grid), dim3(256), 0,
-                           stream, p.ws, C, (long long)ldc, (long long)strideC, (int)M, (int)N, (int)batch,
-                           p.splitK, alpha, beta, bias);
+        if (vec4)
+            hipLaunchKernelGGL(splitk_reduce4_kernel, dim3(grid), dim3(256), 0, stream, p.ws, C, (long long)ldc,
+                               (long long)strideC, (int)M, (int)N, (int)batch, p.splitK, alpha, beta, bias);
+        else
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(grid), dim3(256), 0, stream, p.ws, C, (long long)ldc,
+                               (long long)strideC, (int)M, (int)N, (int)batch, p.splitK, alpha, beta, bias,
+                               out16);
         if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
     }
     return KS_OK;
@@ -458,6 +471,20 @@ extern "C" int ks_gemm_bias(int dtype, int kernel_id, int transA, int transB, in
         if (kernel_id < 0) return kernel_id;
     }
     return run(dtype, kernel_id, KS_GEMM_PASS, bias);
+}
+
+extern "C" int ks_gemm_out_bf16(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                                int64_t K, float alpha, const void *A, int64_t lda, const void *B,
+                                int64_t ldb, float beta, uint16_t *C16, int64_t ldc, const float *bias,
+                                int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                                void *stream) {
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
+    if (kernel_id < 0) {
+        kernel_id = select_checked(dtype, M, N, K, batch, transA, transB);
+        if (kernel_id < 0) return kernel_id;
+    }
+    float *C = reinterpret_cast<float *>(C16);        // element size is carried by the out16 flag
+    return run(dtype, kernel_id, KS_GEMM_PASS, bias, 1);
 }
 
 extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,

@@ -21,8 +21,31 @@ struct GemmParams {
     int tilesM, tilesN;
     int splitK, kChunk;              // K range of split s is [s*kChunk, min(K, (s+1)*kChunk))
     int grid3d;                      // 1: launched as (tilesN, tilesM, batch*splitK) work-groups
+    int out16;                       // 1: C holds bf16 (2-byte elements; ldc in elements); strideC is
+                                     //    then 0 and the batch stride, in elements, is strideC16
+    long long strideC16;
     float alpha, beta;
 };
+
+// bf16 <-> fp32 for an output kept in bf16: widening is exact, narrowing rounds to nearest even
+// (NaN stays NaN)
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+    return __builtin_bit_cast(float, (unsigned)b << 16);
+}
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+// C[idx] = alpha * acc + beta * C[idx] + bias with C in bf16 (element index idx from the batch
+// item's origin)
+__device__ __forceinline__ void store_bf16_out(float *Cb, long long idx, float acc, float alpha, float beta,
+                                               float biasv) {
+    uint16_t *c = reinterpret_cast<uint16_t *>(Cb) + idx;
+    float x = alpha * acc;
+    if (beta != 0.0f) x = fmaf(beta, bf16_bits_to_float(*c), x);
+    *c = float_to_bf16_bits(x + biasv);
+}
 
 // launch shape that tile_of_block expects
 inline dim3 launch_grid(const GemmParams &p, int grid) {
@@ -88,6 +111,15 @@ __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord 
         visit([&](int row, int col, float acc) {
             if (row < M && col < N) w[(long long)row * N + col] = acc;
         });
+    } else if (p.out16) {
+        const float alpha = p.alpha, beta = p.beta;
+        const float *bias = p.bias;
+        const long long ldc = p.ldc;
+        visit([&](int row, int col, float acc) {
+            if (row < M && col < N)
+                store_bf16_out(Cb, (long long)tc.batch * p.strideC16 + (long long)row * ldc + col, acc, alpha,
+                               beta, bias ? bias[col] : 0.0f);
+        });
     } else if (p.bias != nullptr) {
         const float alpha = p.alpha, beta = p.beta;
         const float *bias = p.bias;
@@ -126,6 +158,8 @@ struct OutTarget {
     long long ld;
     float alpha, beta;
     int M, N;
+    int out16;                       // C is bf16 (never set in split-K instantiations)
+    long long off16;                 // element offset of the batch item in a bf16 C
 };
 
 template <bool SPLIT>
@@ -134,9 +168,10 @@ __device__ __forceinline__ OutTarget out_target(const GemmParams &p, const TileC
     o.M = p.M; o.N = p.N;
     if constexpr (SPLIT) {
         o.base = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)p.M * p.N;
-        o.ld = p.N; o.alpha = 1.0f; o.beta = 0.0f; o.bias = nullptr;
+        o.ld = p.N; o.alpha = 1.0f; o.beta = 0.0f; o.bias = nullptr; o.out16 = 0; o.off16 = 0;
     } else {
-        o.base = Cb; o.ld = p.ldc; o.alpha = p.alpha; o.beta = p.beta; o.bias = p.bias;
+        o.base = Cb; o.ld = p.ldc; o.alpha = p.alpha; o.beta = p.beta; o.bias = p.bias; o.out16 = p.out16;
+        o.off16 = (long long)tc.batch * p.strideC16;
     }
     return o;
 }
@@ -148,6 +183,18 @@ __device__ __forceinline__ OutTarget out_target(const GemmParams &p, const TileC
 template <bool SPLIT, int NE, class RowOff>
 __device__ __forceinline__ void store_lane_column(const OutTarget &o, int r0, int col, bool full,
                                                   const float (&v)[NE], RowOff rowOff) {
+    if (!SPLIT && o.out16) {
+        // bf16 output: one form for interior and edge fragments
+        if (col < o.N) {
+            const float bv = o.bias ? o.bias[col] : 0.0f;
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                if (r0 + rowOff(e) < o.M)
+                    store_bf16_out(o.base, o.off16 + (long long)(r0 + rowOff(e)) * o.ld + col, v[e], o.alpha,
+                                   o.beta, bv);
+        }
+        return;
+    }
     float *ptr = o.base + (long long)r0 * o.ld + col;
     if (!SPLIT && o.bias != nullptr) {
         // bias form: the lane's column is fixed, so one bias value serves all its elements
