@@ -322,3 +322,49 @@ def test_seeded_random_small_problems_every_kernel(gpu, dtype):
             prep_workspace(gpu, p, kid)
             check(p, dp.run(kid), ref, "%s case %d (%d x %d x %d, batch %d, tA %d tB %d) kernel %d"
                   % (dtype, case, M, N, K, batch, tA, tB, kid))
+
+
+# ----------------------------------------------------------------------------- K-sliced members, launch shapes
+
+def test_k_sliced_members_with_empty_and_ragged_slices(gpu):
+    """K shorter than the slices of a K-sliced member leaves trailing waves without work; K that
+    is no multiple of 16 cuts the last non-empty slice."""
+    import paper_2003_06795_amd.binding as ks
+    sliced = [k for k in ids_of(gpu, "f32") if ks.kernel_info(ks.F32, k)["k_waves"] > 1]
+    assert len(sliced) >= 8
+    for K in (1, 7, 20, 33, 100, 257):
+        for (tA, tB) in ((0, 0), (1, 1)):
+            p = wl.make_problem("f32", tA, tB, 45, 70, K, batch=2, alpha=1.5, beta=0.5, seed=70 + K, key=tA)
+            dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+            for kid in sliced:
+                prep_workspace(gpu, p, kid)
+                check(p, dp.run(kid), ref, "K-sliced kernel %d, K = %d, layout %d%d" % (kid, K, tA, tB))
+
+
+def test_both_launch_shapes_agree_bitwise(gpu):
+    """Small grids with small operands are launched three-dimensional, everything else as a
+    renumbered one-dimensional grid; a batch count moves the same tiles from one form to the
+    other (the operand bytes grow past the bound), and every batch item must come out the same."""
+    import torch
+    import paper_2003_06795_amd.binding as ks
+    M, N, K = 96, 80, 136
+    g = torch.Generator(device="cuda").manual_seed(5)
+    A = torch.rand(M * K, device="cuda", generator=g) - 0.5
+    B = torch.rand(K * N, device="cuda", generator=g) - 0.5
+    for kid in (1, 5, 22, 28, 35, 36, 43, 58):
+        one = torch.zeros(M * N, device="cuda")
+        ks.gemm_f32_with_kernel(kid, 0, 0, M, N, K, 1.0, A, K, B, N, 0.0, one, N)            # 3-D launch
+        batch = 64                                                                            # 64 x 94 KiB of operands
+        need = ks.workspace_bytes_needed(ks.F32, kid, M, N, batch)
+        if need:
+            gpu.ensure_workspace(need)
+        Ab, Bb = A.repeat(batch), B.repeat(batch)
+        many = torch.zeros(batch * M * N, device="cuda")
+        ks.gemm_f32_with_kernel(kid, 0, 0, M, N, K, 1.0, Ab, K, Bb, N, 0.0, many, N, batch, M * K, K * N, M * N)
+        torch.cuda.synchronize()
+        got = many.view(batch, M * N)
+        info = ks.kernel_info(ks.F32, kid)
+        if info["split_k"] == 1:
+            assert torch.equal(got, one.expand(batch, M * N)), "kernel %d" % kid
+        else:   # a per-call split may pick another partition count for the batched call
+            assert torch.allclose(got, one.expand(batch, M * N), atol=1e-4), "kernel %d" % kid
