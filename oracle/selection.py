@@ -238,6 +238,26 @@ def prune_and_train(X_train, P_train, n_kept, max_depth=12, min_samples_leaf=1):
     return dict(regression_tree=reg, kept=kept, labels=y, selector=clf)
 
 
+def sampled_prune_and_train(X_train, P_train, stage1_rows, n_kept, max_depth=12, min_samples_leaf=1):
+    """A two-stage form of the same pipeline for a configuration space too large to time in full
+    (the paper's conclusion names this as the open problem; the reading is ours): only the rows
+    in `stage1_rows` (boolean mask) are timed for every configuration and decide the kept set;
+    every other training row is timed for the kept configurations only.  The classifier is then
+    fitted on all training rows, labelled inside the kept set.  Entries of P_train that the
+    procedure never measures (non-kept columns of rows outside stage 1) are not read.
+    Returns the kept set, the selector and the number of timed cells."""
+    X_train, P_train = np.asarray(X_train), np.asarray(P_train, dtype=np.float64)
+    m = np.asarray(stage1_rows, dtype=bool)
+    reg = fit_regression_tree(X_train[m], normalise(P_train[m]), n_kept)
+    kept = kept_set(reg)
+    measured = np.zeros_like(P_train)
+    measured[:, kept] = P_train[:, kept]
+    y = labels_within(measured, kept)
+    clf = fit_classification_tree(X_train, y, max_depth, min_samples_leaf)
+    cells = int(m.sum()) * P_train.shape[1] + int((~m).sum()) * len(kept)
+    return dict(kept=kept, selector=clf, timed_cells=cells, regression_tree=reg)
+
+
 # ----------------------------------------------------------------- the other pruning methods
 # Section III compares the decision tree with: the N configurations that win most often, k-means
 # on the normalised performance vectors, k-means in PCA coordinates with the centroids mapped back,

@@ -45,6 +45,31 @@ def other_classifiers(Xtr, ytr, Xte):
     return out
 
 
+def hdbscan_pruning(Ph_tr, Ph_te):
+    """Section III's density-clustering pruner, as a report only: like the paper it uses a library
+    (scikit-learn's HDBSCAN, when importable).  The number of clusters is not a parameter, so the
+    minimum cluster size is swept; a cluster's representative is its mean vector, noise rows are
+    left out, and the kept set is the best configuration of each representative."""
+    try:
+        from sklearn.cluster import HDBSCAN
+    except ImportError:
+        return []
+    out, seen = [], set()
+    for mcs in (2, 3, 4, 5, 6, 8, 10, 15, 20, 30, 40):
+        labels = HDBSCAN(min_cluster_size=mcs).fit_predict(Ph_tr)
+        ids = sorted(set(int(l) for l in labels if l >= 0))
+        if not ids:
+            continue
+        kept = np.unique([int(np.argmax(Ph_tr[labels == l].mean(axis=0))) for l in ids]).astype(np.int32)
+        key = tuple(kept.tolist())
+        if key in seen:
+            continue
+        seen.add(key)
+        out.append(dict(min_cluster_size=mcs, clusters=len(ids), noise_rows=int((labels < 0).sum()),
+                        kept=kept.tolist(), achievable=ks.tune_achievable(Ph_te, kept)))
+    return sorted(out, key=lambda r: len(r["kept"]))
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
@@ -88,6 +113,10 @@ def main(argv=None):
         report["pruning"].append(row)
         print("%3d %9.4f %9.4f %9.4f %9.4f" % (n, row["top_n"]["achievable"], row["kmeans"]["achievable"],
                                                row["pca_kmeans"]["achievable"], row["tree"]["achievable"]))
+    report["hdbscan"] = hdbscan_pruning(Ph_tr, Ph_te)
+    for r in report["hdbscan"]:
+        print("HDBSCAN min_cluster_size %2d: %2d clusters, %3d noise rows, %2d kernels kept, achievable %.4f"
+              % (r["min_cluster_size"], r["clusters"], r["noise_rows"], len(r["kept"]), r["achievable"]))
     for n in (5, 6, 8, 15):
         kept = ks.tune_prune_tree(X[tr], Ph_tr, n)[0]
         tree = ks.tune_fit_selector(X[tr], P[tr], kept)

@@ -116,3 +116,35 @@ def test_bad_arguments():
         ks.tune_selector_score(ks.tune_normalise(P), np.full(20, 4))
     with pytest.raises(ks.KsError):
         ks.tune_normalise(np.zeros((3, 3)))
+
+
+def test_sampled_two_stage_fit_matches_oracle_and_reads_only_timed_cells():
+    from paper_2003_06795_amd.tune import sampled
+    X, P = table(260, 24, 7)
+    Xtr, Ptr, Xte, Pte = X[:200], P[:200], X[200:], P[200:]
+    mask = np.zeros(200, dtype=bool)
+    mask[np.random.default_rng(3).permutation(200)[:60]] = True
+    for n_kept in (4, 8):
+        kept, tree, cells = sampled.sampled_fit(Xtr, Ptr, mask, n_kept)
+        ref = sel.sampled_prune_and_train(Xtr, Ptr, mask, n_kept)
+        assert kept.tolist() == ref["kept"] and cells == ref["timed_cells"]
+        assert cells == 60 * 24 + 140 * len(kept) < 200 * 24
+        assert np.array_equal(ks.tune_predict(tree, Xte), sel.predict_labels(ref["selector"], Xte))
+        # cells the procedure does not time cannot influence the result
+        poisoned = Ptr.copy()
+        untimed = np.ones_like(poisoned, dtype=bool)
+        untimed[mask, :] = False
+        untimed[:, kept] = False
+        poisoned[untimed] = 1e9
+        kept2, tree2, _ = sampled.sampled_fit(Xtr, poisoned, mask, n_kept)
+        assert kept2.tolist() == kept.tolist()
+        assert np.array_equal(ks.tune_predict(tree2, Xte), ks.tune_predict(tree, Xte))
+    # with every row in stage 1 it is the full pipeline
+    kept, tree, cells = sampled.sampled_fit(Xtr, Ptr, np.ones(200, dtype=bool), 6)
+    full = sel.prune_and_train(Xtr, Ptr, 6)
+    assert kept.tolist() == full["kept"] and cells == 200 * 24
+    assert np.array_equal(ks.tune_predict(tree, Xte), sel.predict_labels(full["selector"], Xte))
+    # the stage-1 draw keeps the layouts of a shape together and is reproducible
+    rows = [dict(config=2, M=8 * (i // 4 + 1), N=16, K=32, batch=1) for i in range(80)]
+    m1, m2 = sampled.stage1_mask(rows, 0.25, 1), sampled.stage1_mask(rows, 0.25, 1)
+    assert np.array_equal(m1, m2) and m1.sum() == 20 and np.all(m1.reshape(20, 4).all(axis=1) == m1.reshape(20, 4).any(axis=1))
