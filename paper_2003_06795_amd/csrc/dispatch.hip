@@ -38,7 +38,7 @@ const InstanceDesc kF32[kNumF32] = {
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK)                              \
     {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), SPLITK, \
      KS_CORE_OF_##CORE == KS_CORE_DIRECT ? 0 : KS_CORE_OF_##CORE == KS_CORE_KSLICE ? P1 * BM * BN * 4 \
-                                             : 2 * BK * ((BM + 4) + (BN + 4)) * 4},
+                                             : 2 * BK * ((BM + (BK < 16 ? 64 / BK : 4)) + (BN + (BK < 16 ? 64 / BK : 4))) * 4},
 #include "instances.def"
 #undef KS_F32_INSTANCE
 };

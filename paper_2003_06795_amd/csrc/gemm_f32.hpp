@@ -53,7 +53,14 @@ struct TileLoader {
     static constexpr int OUTER = KC ? ROWS : BK;
     static constexpr int UNITS = INNER * OUTER;
     static constexpr int ITERS = (UNITS + NT - 1) / NT;
-    static constexpr int LDS_LD = ROWS + 4;
+    // Row padding of the LDS tile.  A K-contiguous operand fetched as float4 is written as four
+    // scalars to rows k .. k+3; a wave's lanes then differ in k by multiples of 4 (BK/4 lanes)
+    // and in the row, and land in 64 different banks when 4 * LDS_LD = 256/BK (mod 64), i.e. a
+    // padding of 64/BK floats.  The other forms write along a row and take the padding of 4 that
+    // keeps their 16-byte writes aligned.  (Measured: bank-conflict cycles of the 128 x 128 x 32
+    // member fell to a third and the BK = 32 / 64 members gained 2 - 20 % on long K; giving the
+    // lane groups of an MFMA read rows 4 or 8 apart instead of adjacent ones changed nothing.)
+    static constexpr int LDS_LD = ROWS + ((KC && VEC) ? (BK >= 64 ? 1 : 64 / BK) : 4);
     static_assert((INNER <= NT && NT % INNER == 0) || (INNER > NT && INNER % NT == 0), "walk");
 
     float reg[ITERS][W];
@@ -116,7 +123,7 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
     const GemmParams p) {
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
     constexpr int NT = Shape::threads;
-    constexpr int LDA = BM + 4, LDB = BN + 4;
+    constexpr int LDA = TileLoader<BM, BK, NT, AKC, VEC>::LDS_LD, LDB = TileLoader<BN, BK, NT, BKC, VEC>::LDS_LD;
     __shared__ __attribute__((aligned(16))) float As[2][BK * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
 
