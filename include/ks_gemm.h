@@ -70,8 +70,10 @@ typedef struct {
                             per call: enough partitions to fill the device, fewer if the registered
                             workspace is smaller, none without a workspace) */
     int32_t lds_bytes;   /* static LDS of the instantiation (both stages) */
-    int32_t k_waves;     /* K slices inside one work-group, one wave each, summed through LDS
-                            (core KS_CORE_KSLICE; 1 for every other core) */
+    int32_t k_waves;     /* K slices inside one work-group, summed through LDS at the end: one wave per
+                            slice and wave tile for core KS_CORE_KSLICE, one complete group of waves
+                            (threads / k_waves lanes, its own LDS stages) per slice for the LDS-staged
+                            MFMA cores; 1 = none */
 } ks_kernel_info_t;
 
 /* Node of a deployed decision tree (Section IV: nested integer comparisons).

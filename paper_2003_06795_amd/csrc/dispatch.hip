@@ -35,18 +35,25 @@ constexpr int KS_CORE_OF_FMA = KS_CORE_FMA, KS_CORE_OF_MFMA16 = KS_CORE_MFMA16,
               KS_CORE_OF_KSLICE = KS_CORE_KSLICE;
 
 const InstanceDesc kF32[kNumF32] = {
-#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK)                              \
-    {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), SPLITK, \
-     KS_CORE_OF_##CORE == KS_CORE_DIRECT ? 0 : KS_CORE_OF_##CORE == KS_CORE_KSLICE ? P1 * BM * BN * 4 \
-                                             : 2 * BK * ((BM + (BK < 16 ? 64 / BK : 4)) + (BN + (BK < 16 ? 64 / BK : 4))) * 4},
+// kw: K groups inside the work-group (K-sliced members: waves along K); LDS-staged members with
+// K groups also hold the float4 units through which the groups' accumulators are added
+#define KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, KW)                                     \
+    {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2) * (KW), SPLITK, \
+     KS_CORE_OF_##CORE == KS_CORE_DIRECT   ? 0                                                          \
+     : KS_CORE_OF_##CORE == KS_CORE_KSLICE ? P1 * BM * BN * 4                                           \
+                                           : (KW) * 2 * BK * ((BM + (BK < 16 ? 64 / BK : 4)) + (BN + (BK < 16 ? 64 / BK : 4))) * 4 + \
+                                                 ((KW) > 1 ? (KW) * BM * BN * 4 : 0),                     \
+     KS_CORE_OF_##CORE == KS_CORE_KSLICE ? P1 : (KW)},
+#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, 1)
 #include "instances.def"
 #undef KS_F32_INSTANCE
+#undef KS_F32_INSTANCE_KW
 };
 
 const InstanceDesc kBf16[kNumBf16] = {
 #define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK)                           \
     {id, (F) == 16 ? KS_CORE_MFMA16 : KS_CORE_MFMA32, BM, BN, BK, WM, WN, 64 * (BM / WM) * (BN / WN), \
-     SPLITK, STAGES * BK * (BM + BN) * 2},
+     SPLITK, STAGES * BK * (BM + BN) * 2, 1},
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 };
@@ -246,7 +253,7 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
     if (d->splitK == 0) {
         // automatic split: as many K partitions as fill the device, at least two K-steps each,
         // and no more than the registered workspace can hold (1 = the plain single-kernel form)
-        const int64_t steps = d->core == KS_CORE_KSLICE ? (kTiles + d->p1 - 1) / d->p1 : kTiles;
+        const int64_t steps = (kTiles + d->kw - 1) / d->kw;
         int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch, steps);
         const size_t per = (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
         if (!g_ws) s = 1;
@@ -337,7 +344,7 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     } else {
         out->wm = d->p1; out->wn = d->p2; out->tm = d->p1 / frag; out->tn = d->p2 / frag;
     }
-    out->k_waves = d->core == KS_CORE_KSLICE ? d->p1 : 1;
+    out->k_waves = d->kw;
     out->threads = d->threads;
     out->split_k = d->splitK;
     out->lds_bytes = d->ldsBytes;

@@ -118,24 +118,36 @@ struct TileLoader {
     }
 };
 
-template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, bool AKC, bool BKC, bool VEC>
-__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gemm_f32_kernel(
+// KW > 1 (MFMA cores): the work-group holds KW groups of waves, each a complete copy of the
+// BM x BN wave arrangement with its own LDS stages, and each takes one slice of the work-group's
+// K range (rounded to whole K-steps).  The groups run the same number of K-steps in lock-step (a
+// short slice pads with zero tiles), then add their accumulators through LDS in group order.
+// More waves per compute unit for the same number of tiles, without a workspace.
+template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, bool AKC, bool BKC, bool VEC,
+          int KW = 1>
+__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW)) void gemm_f32_kernel(
     const GemmParams p) {
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
-    constexpr int NT = Shape::threads;
+    constexpr int NT = Shape::threads;                        // threads of one group
+    static_assert(KW == 1 || CORE != CORE_FMA, "K groups need an MFMA core");
     constexpr int LDA = TileLoader<BM, BK, NT, AKC, VEC>::LDS_LD, LDB = TileLoader<BN, BK, NT, BKC, VEC>::LDS_LD;
-    __shared__ __attribute__((aligned(16))) float As[2][BK * LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
+    __shared__ __attribute__((aligned(16))) float AsAll[KW][2][BK * LDA];
+    __shared__ __attribute__((aligned(16))) float BsAll[KW][2][BK * LDB];
 
-    const int tid = threadIdx.x;
+    const int grp = KW == 1 ? 0 : (int)threadIdx.x / NT;
+    const int tid = KW == 1 ? (int)threadIdx.x : (int)threadIdx.x % NT;
+    float (*As)[BK * LDA] = AsAll[grp];
+    float (*Bs)[BK * LDB] = BsAll[grp];
     const TileCoord tc = tile_of_block(p);
     const int row0 = tc.tm * BM, col0 = tc.tn * BN;
     const float *Ab = static_cast<const float *>(p.A) + (long long)tc.batch * p.strideA;
     const float *Bb = static_cast<const float *>(p.B) + (long long)tc.batch * p.strideB;
     float *Cb = p.C + (long long)tc.batch * p.strideC;
-    const int kBegin = tc.split * p.kChunk;
-    const int kEnd = min(p.K, kBegin + p.kChunk);
-    const int nk = (kEnd - kBegin + BK - 1) / BK;
+    const int kLo = tc.split * p.kChunk, kHi = min(p.K, kLo + p.kChunk);
+    const int slice = KW == 1 ? p.kChunk : ((((kHi - kLo) + KW - 1) / KW + BK - 1) / BK) * BK;
+    const int kBegin = kLo + grp * slice;
+    const int kEnd = min(kHi, kBegin + slice);               // may lie below kBegin: an empty slice
+    const int nk = (min(slice, kHi - kLo) + BK - 1) / BK;     // steps of the longest slice, for all groups
 
     // K-steps in flight between global memory and LDS (each in its own set of staging registers):
     // small tiles are latency-bound - few waves per compute unit, short MFMA runs per K-step - and
@@ -276,6 +288,48 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads)) void gem
 #pragma unroll
                 for (int j = 0; j < P2; ++j) emit(row0 + subM + i, col0 + subN + j, accF[i][j]);
         });
+    } else if constexpr (KW > 1) {
+        // every wave publishes its accumulators as float4 units [group][wave][i][j][chunk][lane];
+        // the units are then dealt out over all threads, summed in group order and stored
+        constexpr int CH = CORE == CORE_MFMA32 ? 4 : 1;       // float4 chunks per fragment and lane
+        constexpr int FRG = CORE == CORE_MFMA32 ? 32 : 16;
+        constexpr int UNITS = (NT / 64) * FM * FN * CH * 64;
+        __shared__ floatx4 part[KW][UNITS];
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int base = (((wave * FM + i) * FN + j) * CH) * 64 + lane;
+                if constexpr (CORE == CORE_MFMA16) {
+                    part[grp][base] = acc16[i][j];
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        part[grp][base + c * 64] = floatx4{acc32[i][j][4 * c], acc32[i][j][4 * c + 1],
+                                                           acc32[i][j][4 * c + 2], acc32[i][j][4 * c + 3]};
+                }
+            }
+        __syncthreads();
+        const OutTarget o = out_target<SPLIT>(p, tc, Cb);
+        for (int u = (int)threadIdx.x; u < UNITS; u += NT * KW) {
+            floatx4 sum = part[0][u];
+#pragma unroll
+            for (int g = 1; g < KW; ++g) sum += part[g][u];
+            const int ul = u & 63;
+            int q = __builtin_amdgcn_readfirstlane(u >> 6);
+            const int c = q % CH; q /= CH;
+            const int j = q % FN; q /= FN;
+            const int i = q % FM;
+            const int w = q / FM;
+            const int fr0 = row0 + (w / (BN / P2)) * P1 + i * FRG, fc0 = col0 + (w % (BN / P2)) * P2 + j * FRG;
+            const bool full = fr0 + FRG <= o.M && fc0 + FRG <= o.N;
+            const float v[4] = {sum[0], sum[1], sum[2], sum[3]};
+            if constexpr (CORE == CORE_MFMA16)
+                store_lane_column<SPLIT, 4>(o, fr0 + 4 * (ul >> 4), fc0 + (ul & 15), full, v, [](int e) { return e; });
+            else
+                store_lane_column<SPLIT, 4>(o, fr0 + 8 * c + 4 * (ul >> 5), fc0 + (ul & 31), full, v,
+                                            [](int e) { return e; });
+        }
     } else if constexpr (CORE == CORE_MFMA16) {
         write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc16);
     } else {

@@ -13,9 +13,9 @@
 
 namespace ks {
 
-template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT>
+template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, int KW>
 static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
-    constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads;
+    constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads * KW;
     const dim3 g = launch_grid(p, grid), b(NT);
 #define KS_V(A, B, V)                                                                                   \
     do {                                                                                                \
@@ -24,7 +24,7 @@ static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStre
         else if constexpr (CORE == CORE_DIRECT)                                                         \
             hipLaunchKernelGGL((gemm_f32_direct_kernel<BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p); \
         else                                                                                            \
-            hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p);  \
+            hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V, KW>), g, b, 0, s, p);  \
     } while (0)
     switch (variant) {
         case 0: KS_V(false, false, false); break;
@@ -40,22 +40,24 @@ static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStre
 }
 
 // SPLITMODE 0: never split-K; 1: always; 2: decided per call (variant bit 3), both forms compiled
-template <int CORE, int BM, int BN, int BK, int P1, int P2, int SPLITMODE>
+template <int CORE, int BM, int BN, int BK, int P1, int P2, int SPLITMODE, int KW>
 static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s) {
     if constexpr (SPLITMODE == 2) {
-        if (variant & 8) launch_f32_fixed<CORE, BM, BN, BK, P1, P2, true>(p, grid, variant & 7, s);
-        else launch_f32_fixed<CORE, BM, BN, BK, P1, P2, false>(p, grid, variant & 7, s);
+        if (variant & 8) launch_f32_fixed<CORE, BM, BN, BK, P1, P2, true, KW>(p, grid, variant & 7, s);
+        else launch_f32_fixed<CORE, BM, BN, BK, P1, P2, false, KW>(p, grid, variant & 7, s);
     } else {
-        launch_f32_fixed<CORE, BM, BN, BK, P1, P2, SPLITMODE == 1>(p, grid, variant & 7, s);
+        launch_f32_fixed<CORE, BM, BN, BK, P1, P2, SPLITMODE == 1, KW>(p, grid, variant & 7, s);
     }
 }
 
 template <int SHARD>
 static void fill(LaunchFn *table) {
-#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0)>;
+#define KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, KW) \
+    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0), KW>;
+#define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, 1)
 #include "instances.def"
 #undef KS_F32_INSTANCE
+#undef KS_F32_INSTANCE_KW
 }
 
 void KS_CAT(register_f32_shard_, KS_SHARD)(LaunchFn *table) { fill<KS_SHARD>(table); }

@@ -8,7 +8,7 @@ namespace ks {
 typedef void (*LaunchFn)(const GemmParams &p, int grid, int variant, hipStream_t stream);
 
 struct InstanceDesc {
-    int id, core, bm, bn, bk, p1, p2, threads, splitK, ldsBytes;
+    int id, core, bm, bn, bk, p1, p2, threads, splitK, ldsBytes, kw;
 };
 
 constexpr int kNumF32 = 64;

@@ -38,7 +38,8 @@ def test_registry_has_64_fp32_kernels_with_dense_ids():
             assert ki["id"] == i and ki["dtype"] == dt
             assert ki["lds_bytes"] <= 160 * 1024 and ki["threads"] in (64, 128, 256, 512, 1024)
             assert ki["bm"] % ki["wm"] == 0 and ki["bn"] % ki["wn"] == 0
-            assert ki["k_waves"] >= 1 and (ki["k_waves"] == 1) == (ki["core_name"] != "kslice")
+            assert ki["k_waves"] >= 1 and (ki["core_name"] != "kslice" or ki["k_waves"] > 1)
+            assert ki["k_waves"] == 1 or ki["core_name"] in ("kslice", "mfma16", "mfma32")
             if ki["core_name"] == "fma":
                 assert ki["threads"] == (ki["bm"] // ki["tm"]) * (ki["bn"] // ki["tn"])
             elif ki["core_name"] == "kslice":
@@ -48,7 +49,7 @@ def test_registry_has_64_fp32_kernels_with_dense_ids():
             else:
                 f = 32 if ki["core_name"] == "mfma32" else 16
                 assert ki["wm"] == ki["tm"] * f and ki["wn"] == ki["tn"] * f
-                assert ki["threads"] == 64 * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"])
+                assert ki["threads"] == 64 * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"]) * ki["k_waves"]
             key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"], ki["k_waves"])
             assert key not in seen, "duplicate instantiation %s" % (key,)
             seen.add(key)
