@@ -37,16 +37,19 @@ def kernel_symbol(ks, dt, kid, tA, tB, vec=True, dma=False):
     if dt == ks.F32 and ki["core_name"] == "direct":
         return "gemm_f32_direct_kernel<%d, %d, %d, %d, %d, %s, %s, %s, %s>" % (
             ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], b(split), b(akc), b(bkc), b(vec))
+    if dt == ks.F32 and ki["core_name"] == "kslice":
+        return "gemm_f32_kslice_kernel<%d, %d, %d, %d, %d, %s, %s, %s, %s>" % (
+            ki["bm"], ki["bn"], ki["bk"], ki["k_waves"], ki["wm"], b(split), b(akc), b(bkc), b(vec))
     if dt == ks.F32:
         p1, p2 = (ki["tm"], ki["tn"]) if ki["core_name"] == "fma" else (ki["wm"], ki["wn"])
-        return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s>" % (
-            ki["core"], ki["bm"], ki["bn"], ki["bk"], p1, p2, b(split), b(akc), b(bkc), b(vec))
+        return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s, %d>" % (
+            ki["core"], ki["bm"], ki["bn"], ki["bk"], p1, p2, b(split), b(akc), b(bkc), b(vec), ki["k_waves"])
     f = 16 if ki["core_name"] == "mfma16" else 32
     if vec and dma:
         stages = ki["lds_bytes"] // (ki["bk"] * (ki["bm"] + ki["bn"]) * 2)
-        return "gemm_bf16_dma_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %s>" % (
+        return "gemm_bf16_dma_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %s, false>" % (
             f, ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], stages, b(split), b(akc), b(bkc))
-    return "gemm_bf16_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s>" % (
+    return "gemm_bf16_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s, false>" % (
         f, ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], b(split), b(akc), b(bkc), b(vec))
 
 
