@@ -27,6 +27,14 @@
  *     stated otherwise; on error nothing is launched and C is untouched.
  *   - No entry point is a CPU fallback: without a HIP device the compute calls
  *     fail with KS_ERR_LAUNCH.
+ *   - Threads: the compute entry points keep no per-call host state and may be
+ *     called from several host threads (each on its own stream) at once, with
+ *     one exception: the registered workspace is a single buffer, so two GEMMs
+ *     that both run a split-K member must not be in flight together (same
+ *     stream, or ordered by the caller).  ks_set_workspace, ks_set_fast_path,
+ *     ks_set_tiles_per_workgroup,
+ *     ks_set_selector and ks_time_gemm are not thread-safe.  The library acts
+ *     on the calling thread's current HIP device and never changes it.
  */
 #ifndef KS_GEMM_H
 #define KS_GEMM_H
@@ -204,6 +212,14 @@ int ks_get_selector(int dtype, ks_tree_node_t *nodes, int cap);
  * the generic path (for testing it at aligned shapes); nonzero restores the default. */
 int ks_set_fast_path(int enabled);
 
+/* The large-tile fp32 32x32-MFMA members (LDS-staged, tile of at least 8192 entries and 128 columns, wave
+ * tile of at most 2048, one K group) have a second form in which a work-group walks several consecutive tiles, requesting the next tile's operands before the
+ * finished tile's C is stored; a one-dimensional launch without split-K does so with a count
+ * chosen per call from the tile count and K.  n == 0 restores that default; 1 <= n <= 64 forces
+ * the count (1 = every work-group one tile) for testing and tuning.  Results do not depend on it
+ * (every tile is computed the same way whoever walks it).  Not thread-safe. */
+int ks_set_tiles_per_workgroup(int n);
+
 /* Measurement aid: copies `bytes` (a multiple of 16; both device pointers 16-byte aligned) with a
  * plain one-read-one-write kernel (ks::copy_kernel).  Hardware traffic counters collected over a
  * profile that contains this launch are scaled by what they report for it. */
@@ -212,7 +228,8 @@ int ks_calibration_copy(void *dst_device, const void *src_device, size_t bytes, 
 /* ---------------------------------------------------------------- workspace
  * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no
  * atomics) need split_k * batch * M * N floats of scratch.  The caller registers one device
- * buffer per process; NULL / 0 unregisters.  Kernels with split_k == 1 never touch it. */
+ * buffer per process (at least 4-byte aligned; 16-byte alignment lets the reduction pass use
+ * 16-byte accesses); NULL / 0 unregisters.  Kernels with split_k == 1 never touch it. */
 int ks_set_workspace(void *device_ptr, size_t bytes);
 /* Bytes the kernel would like for this output size (for split_k == 0 the most it can use). */
 size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N, int64_t batch);

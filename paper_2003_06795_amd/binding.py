@@ -54,7 +54,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
     "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
-    "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_workspace", "ks_workspace_bytes_needed",
+    "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
     "ks_tune_pca_variance", "ks_status_string",
@@ -92,6 +92,7 @@ def lib():
     L.ks_get_selector.argtypes = [_i, _p, _i]
     L.ks_calibration_copy.argtypes = [_p, _p, ctypes.c_size_t, _p]
     L.ks_set_fast_path.argtypes = [_i]
+    L.ks_set_tiles_per_workgroup.argtypes = [_i]
     L.ks_set_workspace.argtypes = [_p, ctypes.c_size_t]
     L.ks_workspace_bytes_needed.argtypes = [_i, _i, _i64, _i64, _i64]
     L.ks_workspace_bytes_needed.restype = ctypes.c_size_t
@@ -268,6 +269,11 @@ def calibration_copy(dst, src, nbytes, stream=None):
 
 def set_fast_path(enabled):
     _check(lib().ks_set_fast_path(int(bool(enabled))), "ks_set_fast_path")
+
+
+def set_tiles_per_workgroup(n):
+    """0: chosen per call; 1..64: forced (large-tile fp32 MFMA members, 1-D launches without split-K)."""
+    _check(lib().ks_set_tiles_per_workgroup(int(n)), "ks_set_tiles_per_workgroup")
 
 
 def set_workspace(buf, nbytes=None):

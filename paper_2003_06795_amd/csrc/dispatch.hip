@@ -87,6 +87,7 @@ void init_tables() {
 }
 
 int g_forceGeneric = 0;
+int g_tilesPerWG = 0;        // 0: chosen per call (multi_tiles); n >= 1: forced
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
@@ -113,6 +114,22 @@ int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles) {
         if (bestCost < 0 || cost < bestCost) { bestCost = cost; best = s; }
     }
     return best;
+}
+
+// Tiles one work-group of a multi-tile fp32 member walks.  Walking T tiles takes the work-group
+// launch, the pipeline fill and part of the wait behind the previous tile's stores out of T - 1 of
+// T tiles, but leaves T times fewer work-groups to balance over the compute units, and the
+// flattened loop itself is about 5 % slower per K-step.  Measured on outputs of 0.2 - 3.3 GB with
+// T = 4 .. 8: 7 - 25 % faster when a tile has one K-step, 0 - 7 % with two, 5 % slower from four
+// on; slower as soon as the launch has fewer than about ten rounds of work-groups.  Hence: only
+// for tiles of at most two K-steps and at least 32 rounds of single-tile work-groups, and then so
+// that 8 rounds remain (at most 8 tiles).
+int multi_tiles(const InstanceDesc *d, int64_t tiles, int64_t K) {
+    const int64_t waves = d->threads / 64;
+    const int64_t slots = 256 * (12 / waves > 0 ? 12 / waves : 1);
+    const int64_t rounds = tiles / slots;
+    if (K > 2 * d->bk || rounds < 32) return 1;
+    return (int)(rounds / 8 < 8 ? rounds / 8 : 8);
 }
 
 const InstanceDesc *desc_of(int dtype, int id) {
@@ -202,6 +219,9 @@ int validate(int transA, int transB, int64_t M, int64_t N, int64_t K, const void
     if (M < 0 || N < 0 || K < 0 || batch < 0) return KS_ERR_INVALID_ARG;
     const int64_t lim = 2147483647LL - 512;
     if (M >= lim || N >= lim || K >= lim || batch >= lim) return KS_ERR_UNSUPPORTED;
+    // leading dimensions take part in 64-bit element offsets (row * ld): keep the products far from overflow
+    const int64_t ldLim = 1LL << 40;
+    if (lda >= ldLim || ldb >= ldLim || ldc >= ldLim) return KS_ERR_UNSUPPORTED;
     if (M == 0 || N == 0 || batch == 0) return KS_OK;
     if (!C || ldc < N) return KS_ERR_INVALID_ARG;
     if (K > 0) {
@@ -263,15 +283,20 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
     p.kChunk = (int)(((kTiles + p.splitK - 1) / p.splitK) * d->bk);
     p.alpha = alpha; p.beta = beta;
 
-    const int64_t grid64 = (int64_t)p.tilesM * p.tilesN * batch * p.splitK;
+    int64_t grid64 = (int64_t)p.tilesM * p.tilesN * batch * p.splitK;
     if (grid64 > 2147483647LL) return KS_ERR_UNSUPPORTED;
     // three-dimensional launch only where the tile order cannot matter for L2: few work-groups
     // and operands that fit one XCD's L2 several times over
-    const int64_t operandBytes = (M + N) * K * batch * (dtype == KS_F32 ? 4 : 2);
-    p.grid3d = grid64 <= KS_GRID3D_MAX && operandBytes <= KS_GRID3D_BYTES && p.tilesM <= 65535 &&
+    const double operandBytes = (double)(M + N) * (double)K * (double)batch * (dtype == KS_F32 ? 4 : 2);
+    p.grid3d = grid64 <= KS_GRID3D_MAX && operandBytes <= (double)KS_GRID3D_BYTES && p.tilesM <= 65535 &&
                        batch * p.splitK <= 65535
                    ? 1
                    : 0;
+    p.tilesPerWG = 1;
+    if (dtype == KS_F32 && !p.grid3d && p.splitK == 1 && f32_multi_tile(d->core, d->bm, d->bn, d->p1, d->p2, d->kw)) {
+        p.tilesPerWG = g_tilesPerWG > 0 ? g_tilesPerWG : multi_tiles(d, grid64, K);
+        grid64 = (grid64 + p.tilesPerWG - 1) / p.tilesPerWG;
+    }
 
     if (p.splitK > 1) {
         const size_t need = (size_t)p.splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
@@ -368,12 +393,19 @@ extern "C" int ks_set_fast_path(int enabled) {
     return KS_OK;
 }
 
+extern "C" int ks_set_tiles_per_workgroup(int n) {
+    if (n < 0 || n > 64) return KS_ERR_INVALID_ARG;
+    g_tilesPerWG = n;
+    return KS_OK;
+}
+
 extern "C" int ks_set_workspace(void *device_ptr, size_t bytes) {
     if (device_ptr == nullptr || bytes == 0) {
         g_ws = nullptr;
         g_wsBytes = 0;
         return KS_OK;
     }
+    if (reinterpret_cast<uintptr_t>(device_ptr) % sizeof(float)) return KS_ERR_INVALID_ARG;
     g_ws = device_ptr;
     g_wsBytes = bytes;
     return KS_OK;

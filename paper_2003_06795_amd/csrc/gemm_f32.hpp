@@ -33,6 +33,14 @@ namespace ks {
     ((regs) <= 8 || ((regs) <= 16 && (threads) <= 256) ? 4 : (regs) <= 32 ? 2 : 1)
 #endif
 
+// Waves per SIMD the register allocation must leave room for (0 = no demand).  The multi-tile
+// forms keep the next tile's staging registers alive across the epilogue; the four-wave members
+// with 64 x 32 wave tiles then drift a few registers past the budget of three waves per SIMD (168
+// with the accumulators) that they met before, and lose a resident work-group.
+#ifndef KS_F32_MIN_WAVES
+#define KS_F32_MIN_WAVES(multi, core, bm, bn, bk, p1, p2) ((multi) && ((bm) / (p1)) * ((bn) / (p2)) <= 4 ? 3 : 0)
+#endif
+
 enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3, CORE_KSLICE = 4 };
 
 template <int CORE, int BM, int BN, int P1, int P2>
@@ -123,10 +131,15 @@ struct TileLoader {
 // K range (rounded to whole K-steps).  The groups run the same number of K-steps in lock-step (a
 // short slice pads with zero tiles), then add their accumulators through LDS in group order.
 // More waves per compute unit for the same number of tiles, without a workspace.
+//
+// MULTI (members for which f32_multi_tile holds, never split-K): the work-group walks
+// GemmParams::tilesPerWG consecutive logical tiles.  The single-tile form of the same member is a
+// separate instantiation: the flattened loop costs it about 6 % on ordinary shapes.
 template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, bool AKC, bool BKC, bool VEC,
-          int KW = 1>
-__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW)) void gemm_f32_kernel(
+          int KW = 1, bool MULTI = false>
+__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), KS_F32_MIN_WAVES(MULTI, CORE, BM, BN, BK, P1, P2)) void gemm_f32_kernel(
     const GemmParams p) {
+    static_assert(!MULTI || (f32_multi_tile(CORE, BM, BN, P1, P2, KW) && !SPLIT), "multi-tile form");
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
     constexpr int NT = Shape::threads;                        // threads of one group
     static_assert(KW == 1 || CORE != CORE_FMA, "K groups need an MFMA core");
@@ -138,7 +151,9 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW)) voi
     const int tid = KW == 1 ? (int)threadIdx.x : (int)threadIdx.x % NT;
     float (*As)[BK * LDA] = AsAll[grp];
     float (*Bs)[BK * LDB] = BsAll[grp];
-    const TileCoord tc = tile_of_block(p);
+    // the (first) tile of this work-group
+    const TileCoord tc = MULTI && !p.grid3d ? tile_of_logical(p, logical_of_block() * (unsigned)p.tilesPerWG)
+                                            : tile_of_block(p);
     const int row0 = tc.tm * BM, col0 = tc.tn * BN;
     const float *Ab = static_cast<const float *>(p.A) + (long long)tc.batch * p.strideA;
     const float *Bb = static_cast<const float *>(p.B) + (long long)tc.batch * p.strideB;
@@ -244,6 +259,79 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW)) voi
             }
         }
     };
+
+    if constexpr (MULTI) {
+        // The work-group walks nTiles consecutive logical tiles as ONE sequence of K-steps: the
+        // loads run PF steps ahead of the MFMAs across tile boundaries, so the first steps of the
+        // next tile are requested before the finished tile's C is stored (the vector memory path
+        // of a compute unit is in order: loads issued behind 64 KB of stores to a busy HBM wait
+        // for them), and tiles after the first pay no work-group launch and no pipeline fill.
+        // All tiles of a launch with tilesPerWG > 1 share one K range (the host grants it only
+        // without split-K); a range without steps still runs one step of zero tiles.
+        unsigned firstTile = 0;
+        int nTiles = 1;
+        if (!p.grid3d) {
+            const unsigned total = (unsigned)p.tilesM * (unsigned)p.tilesN * (unsigned)(p.batch * p.splitK);
+            firstTile = logical_of_block() * (unsigned)p.tilesPerWG;
+            nTiles = (int)min((unsigned)p.tilesPerWG, total - firstTile);
+        }
+        const int nkT = max(nk, 1);
+        const int G = nTiles * nkT;
+        // load stream
+        TileCoord tcL = tc;
+        int iL = 0, kL = 0, rowL = row0, colL = col0;
+        const float *AbL = Ab, *BbL = Bb;
+        auto issue_load = [&](LoaderA &a, LoaderB &b) {
+            a.load(AbL, p.lda, rowL, p.M, kBegin + kL * BK, kEnd, tid);
+            b.load(BbL, p.ldb, colL, p.N, kBegin + kL * BK, kEnd, tid);
+            if (++kL == nkT) {
+                kL = 0;
+                if (++iL < nTiles) {
+                    tcL = tile_of_logical(p, firstTile + (unsigned)iL);
+                    rowL = tcL.tm * BM; colL = tcL.tn * BN;
+                    AbL = static_cast<const float *>(p.A) + (long long)tcL.batch * p.strideA;
+                    BbL = static_cast<const float *>(p.B) + (long long)tcL.batch * p.strideB;
+                }
+            }
+        };
+        // compute stream
+        TileCoord tcC = tc;
+        int iC = 0, kC = 0;
+#pragma unroll
+        for (int d = 0; d < PF; ++d)
+            if (d < G) issue_load(la[d], lb[d]);
+        la[0].store(As[0], tid);
+        lb[0].store(Bs[0], tid);
+        __syncthreads();
+        for (int g0 = 0; g0 < G; g0 += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int g = g0 + u;
+                if (g >= G) break;
+                const int cur = g & 1;
+                if (g + PF < G) issue_load(la[u], lb[u]);
+                compute_step(As[cur], Bs[cur]);
+                if (g + 1 < G) {
+                    la[(u + 1) % PF].store(As[cur ^ 1], tid);
+                    lb[(u + 1) % PF].store(Bs[cur ^ 1], tid);
+                }
+                if (++kC == nkT) {
+                    kC = 0;
+                    float *Cc = p.C + (long long)tcC.batch * p.strideC;
+                    write_tile_mfma32_lean<SPLIT, FM, FN>(p, tcC, Cc, tcC.tm * BM + subM, tcC.tn * BN + subN, lane, acc32);
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+                    if (++iC < nTiles) tcC = tile_of_logical(p, firstTile + (unsigned)iC);
+                }
+                __syncthreads();
+            }
+        }
+        return;
+    }
 
 #pragma unroll
     for (int d = 0; d < PF; ++d)

@@ -16,6 +16,8 @@ namespace ks {
 template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, int KW>
 static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
     constexpr int NT = F32Shape<CORE, BM, BN, P1, P2>::threads * KW;
+    // the multi-tile form exists beside the single-tile one and runs when the host asks for it
+    constexpr bool MULTI_OK = !SPLIT && f32_multi_tile(CORE, BM, BN, P1, P2, KW);
     const dim3 g = launch_grid(p, grid), b(NT);
 #define KS_V(A, B, V)                                                                                   \
     do {                                                                                                \
@@ -23,7 +25,12 @@ static void launch_f32_fixed(const GemmParams &p, int grid, int variant, hipStre
             hipLaunchKernelGGL((gemm_f32_kslice_kernel<BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p); \
         else if constexpr (CORE == CORE_DIRECT)                                                         \
             hipLaunchKernelGGL((gemm_f32_direct_kernel<BM, BN, BK, P1, P2, SPLIT, A, B, V>), g, b, 0, s, p); \
-        else                                                                                            \
+        else if constexpr (MULTI_OK) {                                                                  \
+            if (p.tilesPerWG > 1)                                                                       \
+                hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V, KW, true>), g, b, 0, s, p); \
+            else                                                                                        \
+                hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V, KW>), g, b, 0, s, p); \
+        } else                                                                                          \
             hipLaunchKernelGGL((gemm_f32_kernel<CORE, BM, BN, BK, P1, P2, SPLIT, A, B, V, KW>), g, b, 0, s, p);  \
     } while (0)
     switch (variant) {

@@ -21,6 +21,8 @@ struct GemmParams {
     int tilesM, tilesN;
     int splitK, kChunk;              // K range of split s is [s*kChunk, min(K, (s+1)*kChunk))
     int grid3d;                      // 1: launched as (tilesN, tilesM, batch*splitK) work-groups
+    int tilesPerWG;                  // consecutive logical tiles one work-group walks (members that
+                                     // support it; 1 everywhere else and on 3-D launches)
     int out16;                       // 1: C holds bf16 (2-byte elements; ldc in elements); strideC is
                                      //    then 0 and the batch stride, in elements, is strideC16
     long long strideC16;
@@ -47,6 +49,14 @@ __device__ __forceinline__ void store_bf16_out(float *Cb, long long idx, float a
     *c = float_to_bf16_bits(x + biasv);
 }
 
+// fp32 LDS-staged members that also exist in a form whose work-groups walk several tiles
+// (GemmParams::tilesPerWG): 32x32 MFMA members (core 2) with large tiles of at least 128 columns
+// (the 128 x 64 member measured slower in that form), wave tiles of at most 2048 entries (the form
+// holds staging registers across the epilogue) and a single K group.
+constexpr bool f32_multi_tile(int core, int bm, int bn, int p1, int p2, int kw) {
+    return core == 2 && bm * bn >= 8192 && bn >= 128 && p1 * p2 <= 2048 && kw == 1;
+}
+
 // launch shape that tile_of_block expects
 inline dim3 launch_grid(const GemmParams &p, int grid) {
     return p.grid3d ? dim3((unsigned)p.tilesN, (unsigned)p.tilesM, (unsigned)(p.batch * p.splitK))
@@ -63,6 +73,29 @@ struct TileCoord {
 // compact block that shares A row-panels and B column-panels in that XCD's L2.
 // Small grids (where a handful of integer divisions is a visible part of a 3 us kernel and L2
 // locality is not at stake) are launched three-dimensional instead and read their tile directly.
+__device__ __forceinline__ unsigned logical_of_block() {
+    const unsigned total = gridDim.x, id = blockIdx.x;
+    const unsigned q = total >> 3, r = total & 7u, x = id & 7u;
+    return x * q + (x < r ? x : r) + (id >> 3);
+}
+
+// tile with logical id `logical` of a one-dimensional launch: units (batch item, K partition) in
+// order, inside a unit bands of 8 tile-rows walked column-major
+__device__ __forceinline__ TileCoord tile_of_logical(const GemmParams &p, unsigned logical) {
+    const unsigned per = (unsigned)p.tilesM * (unsigned)p.tilesN;
+    const unsigned unit = logical / per, t = logical - unit * per;
+    TileCoord c;
+    c.batch = (int)(unit / (unsigned)p.splitK);
+    c.split = (int)(unit - (unsigned)c.batch * (unsigned)p.splitK);
+    const unsigned band = 8u * (unsigned)p.tilesN;
+    const unsigned g = t / band, in = t - g * band;
+    const unsigned first = g * 8u;
+    const unsigned rows = ((unsigned)p.tilesM - first) < 8u ? ((unsigned)p.tilesM - first) : 8u;
+    c.tn = (int)(in / rows);
+    c.tm = (int)(first + (in - (unsigned)c.tn * rows));
+    return c;
+}
+
 __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
     if (p.grid3d) {
         TileCoord c;
@@ -77,21 +110,7 @@ __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
         }
         return c;
     }
-    const unsigned total = gridDim.x, id = blockIdx.x;
-    const unsigned q = total >> 3, r = total & 7u, x = id & 7u;
-    const unsigned logical = x * q + (x < r ? x : r) + (id >> 3);
-    const unsigned per = (unsigned)p.tilesM * (unsigned)p.tilesN;
-    const unsigned unit = logical / per, t = logical - unit * per;
-    TileCoord c;
-    c.batch = (int)(unit / (unsigned)p.splitK);
-    c.split = (int)(unit - (unsigned)c.batch * (unsigned)p.splitK);
-    const unsigned band = 8u * (unsigned)p.tilesN;
-    const unsigned g = t / band, in = t - g * band;
-    const unsigned first = g * 8u;
-    const unsigned rows = ((unsigned)p.tilesM - first) < 8u ? ((unsigned)p.tilesM - first) : 8u;
-    c.tn = (int)(in / rows);
-    c.tm = (int)(first + (in - (unsigned)c.tn * rows));
-    return c;
+    return tile_of_logical(p, logical_of_block());
 }
 
 // Epilogue.  `visit(f)` calls f(row, col, acc) for every accumulator element this lane owns
@@ -272,6 +291,29 @@ __device__ __forceinline__ void write_tile_mfma32(const GemmParams &p, const Til
             for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
             store_lane_column<SPLIT, 16>(o, rb + i * 32 + 4 * (lane >> 5), cb + j * 32 + (lane & 31), full, v,
                                          [](int e) { return 8 * (e >> 2) + (e & 3); });
+        }
+}
+
+// The same fragment layout written in four chunks of four rows with the scheduler kept from
+// merging them: fewer addresses and old values alive at once, for kernels that hold other
+// registers (the next tile's operands) across the epilogue.
+template <bool SPLIT, int FM, int FN, class Acc>
+__device__ __forceinline__ void write_tile_mfma32_lean(const GemmParams &p, const TileCoord &tc, float *Cb,
+                                                       int rowBase, int colBase, int lane, const Acc &acc) {
+    const OutTarget o = out_target<SPLIT>(p, tc, Cb);
+    const int rb = __builtin_amdgcn_readfirstlane(rowBase), cb = __builtin_amdgcn_readfirstlane(colBase);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const bool full = rb + i * 32 + 32 <= o.M && cb + j * 32 + 32 <= o.N;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float v[4] = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
+                store_lane_column<SPLIT, 4>(o, rb + i * 32 + 8 * c + 4 * (lane >> 5), cb + j * 32 + (lane & 31), full, v,
+                                            [](int e) { return e; });
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
 }
 

@@ -248,6 +248,12 @@ def test_argument_errors_launch_nothing(gpu):
     with pytest.raises(ks.KsError) as e:
         ks.gemm_f32_with_kernel(**dict(base, M=2 ** 31))
     assert e.value.status == ks.ERR_UNSUPPORTED
+    with pytest.raises(ks.KsError) as e:
+        ks.gemm_f32_with_kernel(**dict(base, ldc=2 ** 40))
+    assert e.value.status == ks.ERR_UNSUPPORTED
+    with pytest.raises(ks.KsError) as e:
+        ks.set_workspace(C.data_ptr() + 2, 64)          # not a float address
+    assert e.value.status == ks.ERR_INVALID_ARG
     ks.set_workspace(None)
     fixed_split = [k for k in range(ks.num_kernels(ks.BF16)) if ks.kernel_info(ks.BF16, k)["split_k"] > 1][0]
     with pytest.raises(ks.KsError) as e:
@@ -368,3 +374,72 @@ def test_both_launch_shapes_agree_bitwise(gpu):
             assert torch.equal(got, one.expand(batch, M * N)), "kernel %d" % kid
         else:   # a per-call split may pick another partition count for the batched call
             assert torch.allclose(got, one.expand(batch, M * N), atol=1e-4), "kernel %d" % kid
+
+
+def multi_tile_members(ks):
+    """fp32 members whose work-groups can walk several tiles: large-tile MFMA, one K group, and
+    (for a launch to do so) not a fixed split-K member."""
+    out = []
+    for k in range(ks.num_kernels(ks.F32)):
+        i = ks.kernel_info(ks.F32, k)
+        if i["core_name"] == "mfma32" and i["bm"] * i["bn"] >= 8192 and i["bn"] >= 128 and i["wm"] * i["wn"] <= 2048 \
+                and i["k_waves"] == 1 and i["split_k"] <= 1:
+            out.append(k)
+    return out
+
+
+def test_work_groups_walking_several_tiles(gpu):
+    """Forced tile counts per work-group (ragged last work-group, tiles crossing batch items, edge
+    tiles) give bit-identical results to one tile per work-group, which matches the oracle."""
+    import paper_2003_06795_amd.binding as ks
+    members = multi_tile_members(ks)
+    assert len(members) >= 4
+    ks.set_workspace(None)                      # per-call split members then run unsplit
+    cases = [
+        dict(transA=0, transB=0, M=300, N=280, K=1100, batch=2, alpha=1.0, beta=0.5),
+        dict(transA=1, transB=1, M=515, N=260, K=1500, batch=1, alpha=-0.5, beta=0.0, pad=(4, 8, 4)),
+        dict(transA=0, transB=1, M=130, N=129, K=2051, batch=3, alpha=1.0, beta=0.0),   # scalar loads
+    ]
+    try:
+        for ci, c in enumerate(cases):
+            c = dict(c)
+            p = wl.make_problem("f32", c.pop("transA"), c.pop("transB"), c.pop("M"), c.pop("N"), c.pop("K"),
+                                seed=21, key=ci, c_fill="uniform", **c)
+            assert (p.M + p.N) * p.K * p.batch * 4 > (4 << 20)     # one-dimensional launch
+            dp = gpu.DeviceProblem(p)
+            ref = gpu.oracle_full(p)
+            for kid in members:
+                ks.set_tiles_per_workgroup(1)
+                one = dp.run(kid)
+                check(p, one, ref, "kernel %d case %d" % (kid, ci))
+                for t in (2, 3, 7, 64):
+                    ks.set_tiles_per_workgroup(t)
+                    assert np.array_equal(dp.run(kid), one), "kernel %d case %d: %d tiles per work-group" % (kid, ci, t)
+    finally:
+        ks.set_tiles_per_workgroup(0)
+        gpu.ensure_workspace.__defaults__[0].clear()
+
+
+def test_several_tiles_with_a_single_short_k_step(gpu):
+    """K shorter than one K-step and thousands of tiles: every step of the flattened loop ends a
+    tile.  Automatic and forced counts agree bitwise; sampled entries match the oracle."""
+    import torch
+    import paper_2003_06795_amd.binding as ks
+    p = wl.make_problem("f32", 0, 0, 6437, 2885, 20, seed=22, c_fill="nan")
+    dp = gpu.DeviceProblem(p)
+    bb, ii, jj = gpu.sample_entries(p, 2048, 5, tile=128)
+    ref = gpu.oracle_entries(p, bb, ii, jj)
+    flat = bb * p.strideC + ii * p.ldc + jj
+    ks.set_workspace(None)
+    try:
+        for kid in multi_tile_members(ks):
+            ks.set_tiles_per_workgroup(1)
+            one = dp.run(kid)
+            assert not np.isnan(one[~c_padding_mask(p)]).any()
+            assert np.max(np.abs(one[flat].astype(np.float64) - ref)) <= tolerance(p), kid
+            for t in (0, 5):
+                ks.set_tiles_per_workgroup(t)
+                assert np.array_equal(dp.run(kid), one), "kernel %d, %d tiles per work-group" % (kid, t)
+    finally:
+        ks.set_tiles_per_workgroup(0)
+        gpu.ensure_workspace.__defaults__[0].clear()
