@@ -443,3 +443,55 @@ def test_several_tiles_with_a_single_short_k_step(gpu):
     finally:
         ks.set_tiles_per_workgroup(0)
         gpu.ensure_workspace.__defaults__[0].clear()
+
+
+def test_several_tiles_with_bias_and_bf16_output(gpu):
+    """The multi-tile form goes through the same bias and bf16-output epilogues: forced tile counts
+    agree bitwise with one tile per work-group, which matches the oracle."""
+    import torch
+    import paper_2003_06795_amd.binding as ks
+    from oracle import gemm as og
+    p = wl.make_problem("f32", 0, 1, 390, 261, 1700, batch=2, alpha=0.75, beta=0.5, seed=23, c_fill="uniform")
+    assert (p.M + p.N) * p.K * p.batch * 4 > (4 << 20)
+    dp = gpu.DeviceProblem(p)
+    bias = (2.0 * wl.uniform_pm1(p.N, 23, 7)).astype(np.float32)
+    bias_dev = torch.from_numpy(bias).cuda()
+    ref = p.C0.copy()
+    og.gemm_bias(p.dtype, p.transA, p.transB, p.M, p.N, p.K, p.alpha, p.A, p.lda, p.B, p.ldb, p.beta, ref,
+                 p.ldc, bias, p.batch, p.strideA, p.strideB, p.strideC)
+    c16 = wl.f32_to_bf16_rne(p.C0)
+    ref16 = c16.copy()
+    og.gemm_out_bf16(p.dtype, p.transA, p.transB, p.M, p.N, p.K, p.alpha, p.A, p.lda, p.B, p.ldb, p.beta, ref16,
+                     p.ldc, bias, p.batch, p.strideA, p.strideB, p.strideC)
+    live = ~c_padding_mask(p)
+    args = (p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb, p.beta)
+    tail = (p.batch, p.strideA, p.strideB, p.strideC)
+
+    def with_bias(kid):
+        C = dp.C0.clone()
+        ks.gemm_bias(ks.F32, kid, *args, C, p.ldc, bias_dev, *tail)
+        torch.cuda.synchronize()
+        return C.cpu().numpy()
+
+    def with_out16(kid):
+        C = torch.from_numpy(c16.view(np.int16).copy()).cuda()
+        ks.gemm_out_bf16(ks.F32, kid, *args, C, p.ldc, bias_dev, *tail)
+        torch.cuda.synchronize()
+        return C.cpu().numpy().view(np.uint16)
+
+    ks.set_workspace(None)
+    try:
+        for kid in multi_tile_members(ks):
+            ks.set_tiles_per_workgroup(1)
+            one, one16 = with_bias(kid), with_out16(kid)
+            tol = tolerance(p) + 2.0 ** -22 * (float(np.max(np.abs(bias))) + float(np.max(np.abs(ref[live]))))
+            assert np.max(np.abs(one[live].astype(np.float64) - ref[live])) <= tol, kid
+            # bf16 output: within one bf16 step of the oracle's rounding of its fp64 value
+            a, b = wl.bf16_to_f32(one16[live]).astype(np.float64), wl.bf16_to_f32(ref16[live]).astype(np.float64)
+            assert np.max(np.abs(a - b) / np.maximum(np.abs(b), 1.0)) <= 2.0 ** -7, kid
+            ks.set_tiles_per_workgroup(3)
+            assert np.array_equal(with_bias(kid), one), kid
+            assert np.array_equal(with_out16(kid), one16), kid
+    finally:
+        ks.set_tiles_per_workgroup(0)
+        gpu.ensure_workspace.__defaults__[0].clear()
