@@ -57,6 +57,10 @@ def rows_of(config, limit=None, seed=0):
     elif config == 7:
         for i, (s, tA, tB, M, N, K, b) in enumerate(wl.config2_extra_rows()):
             out.append((i, "f32", tA, tB, M, N, K, b, 1.0, 0.0))
+    elif config == 11:
+        # more batched small shapes (other dimensions and batch sizes): training only
+        for i, (M, N, K, b) in enumerate(wl.config4_extra_rows()):
+            out.append((i, "f32", 0, 0, M, N, K, b, wl.CONFIG4_ALPHA, wl.CONFIG4_BETA))
     elif config == 6:
         i = 0
         for (M, N, K) in wl.bf16_tuning_shapes():

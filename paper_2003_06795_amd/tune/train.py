@@ -93,6 +93,34 @@ def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted):
     return kept, reg, tree
 
 
+BATCH_FEATURE = 3          # index of `batch` in the ks_features layout
+
+
+def fit_by_regime(Xtr, Ptr, n_single, n_batched, max_depth, min_samples_leaf, weighted):
+    """One pruning + classifier fit per regime (single GEMMs, batch == 1; batched ones, batch > 1),
+    each with its own leaf limit, joined under a root that compares the batch count: the deployed
+    selector stays one tree of nested comparisons (Section IV), but the rows of one regime no
+    longer compete with the other's for the pruning tree's leaves (Section III)."""
+    single = Xtr[:, BATCH_FEATURE] <= 1
+    if single.all() or not single.any():
+        return fit(Xtr, Ptr, n_single, max_depth, min_samples_leaf, weighted)
+    k1, r1, t1 = fit(Xtr[single], Ptr[single], n_single, max_depth, min_samples_leaf, weighted)
+    k2, r2, t2 = fit(Xtr[~single], Ptr[~single], n_batched, max_depth, min_samples_leaf, weighted)
+
+    def join(a, b):
+        out = np.zeros(1 + len(a) + len(b), dtype=ks.TREE_DTYPE)
+        out[0] = (BATCH_FEATURE, 1, 1 + len(a), int(a[0]["value"]), 1)
+        for off, part in ((1, a), (1 + len(a), b)):
+            for i, n in enumerate(part):
+                leaf = n["feature"] < 0
+                out[off + i] = (n["feature"], -1 if leaf else n["left"] + off, -1 if leaf else n["right"] + off,
+                                n["value"], n["threshold"])
+        return out
+
+    kept = np.array(sorted(set(k1.tolist()) | set(k2.tolist())), dtype=k1.dtype)
+    return kept, join(r1, r2), join(t1, t2)
+
+
 def evaluate(tree, kept, X, P):
     Ph = ks.tune_normalise(P)
     chosen = ks.tune_predict(tree, X)
@@ -140,6 +168,9 @@ def main(argv=None):
     ap.add_argument("--features", type=int, default=ks.NUM_RAW_FEATURES,
                     help="length of the feature prefix (6 = raw sizes and flags, 10 = with derived)")
     ap.add_argument("--weighted", action="store_true")
+    ap.add_argument("--n-kept-batched", type=int, default=0,
+                    help="> 0: rows with batch > 1 are pruned and classified on their own with this leaf "
+                         "limit, and the two trees are joined under a root that compares the batch count")
     ap.add_argument("--all-rows", action="store_true", help="train on every row (no held-out set)")
     ap.add_argument("--emit", action="store_true", help="write tree JSON + csrc/selector_table.inc")
     ap.add_argument("--report", default=None)
@@ -160,10 +191,14 @@ def main(argv=None):
     report = dict(dtype=a.dtype, timings=[os.path.relpath(t) for t in a.timings], rows=len(rows),
                   train_rows=int(tr.sum()), test_rows=int(te.sum()), features=a.features,
                   max_depth=a.max_depth, min_samples_leaf=a.min_samples_leaf, weighted=a.weighted,
-                  sweep=[])
+                  n_kept_batched=a.n_kept_batched, sweep=[])
     chosen_fit = None
     for n in sorted({4, 5, 6, 8, 15, a.n_kept}):
-        kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted)
+        if a.n_kept_batched > 0:
+            kept, reg, tree = fit_by_regime(X[tr], P[tr], n, a.n_kept_batched, a.max_depth, a.min_samples_leaf,
+                                            a.weighted)
+        else:
+            kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted)
         ev_tr, ev_te = evaluate(tree, kept, X[tr], P[tr]), evaluate(tree, kept, X[te], P[te])
         per_cfg = {}
         for cfg in sorted({r["config"] for r in rows}):

@@ -148,3 +148,40 @@ def test_sampled_two_stage_fit_matches_oracle_and_reads_only_timed_cells():
     rows = [dict(config=2, M=8 * (i // 4 + 1), N=16, K=32, batch=1) for i in range(80)]
     m1, m2 = sampled.stage1_mask(rows, 0.25, 1), sampled.stage1_mask(rows, 0.25, 1)
     assert np.array_equal(m1, m2) and m1.sum() == 20 and np.all(m1.reshape(20, 4).all(axis=1) == m1.reshape(20, 4).any(axis=1))
+
+
+def test_trees_per_regime_join_under_a_batch_comparison():
+    """train.fit_by_regime: the joined tree answers every row as the tree of its regime does, its
+    kept set is the union, it deploys through ks_set_selector, and rows of one regime cannot
+    change what the other regime's tree says."""
+    from paper_2003_06795_amd.tune import train
+    X, P = table(300, 16, 21)
+    r = np.random.default_rng(3)
+    batched = r.random(len(X)) < 0.3
+    X = X.copy()
+    X[batched, train.BATCH_FEATURE] = r.choice([256, 1024, 4096], int(batched.sum()))
+    P = P.copy()
+    P[batched, 7] += 2e12                      # the batched rows prefer a configuration of their own
+    kept, reg, tree = train.fit_by_regime(X, P, 6, 3, 12, 1, False)
+    k1, _, t1 = train.fit(X[~batched], P[~batched], 6, 12, 1, False)
+    k2, _, t2 = train.fit(X[batched], P[batched], 3, 12, 1, False)
+    assert kept.tolist() == sorted(set(k1.tolist()) | set(k2.tolist()))
+    assert (int(tree[0]["feature"]), int(tree[0]["threshold"])) == (train.BATCH_FEATURE, 1)
+    got = ks.tune_predict(tree, X)
+    assert np.array_equal(got[~batched], ks.tune_predict(t1, X[~batched]))
+    assert np.array_equal(got[batched], ks.tune_predict(t2, X[batched]))
+    assert 7 in k2.tolist()
+    # other batched rows leave the single-GEMM answers alone
+    P2 = P.copy()
+    P2[batched] = P[batched][:, ::-1]
+    tree2 = train.fit_by_regime(X, P2, 6, 3, 12, 1, False)[2]
+    assert np.array_equal(ks.tune_predict(tree2, X[~batched]), got[~batched])
+    try:
+        ks.set_selector(ks.F32, tree)
+        for i in range(0, len(X), 7):
+            M, N, K, b, tA, tB = (int(v) for v in X[i, :6])
+            assert ks.select(ks.F32, M, N, K, b, tA, tB) == int(got[i])
+    finally:
+        ks.set_selector(ks.F32, None)
+    # a table with one regime only falls back to the plain fit
+    assert train.fit_by_regime(X[~batched], P[~batched], 6, 3, 12, 1, False)[2].tobytes() == t1.tobytes()

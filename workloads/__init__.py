@@ -18,7 +18,7 @@ import numpy as np
 __all__ = [
     "Problem", "make_problem", "uniform_pm1", "normal_scaled", "f32_to_bf16_rne",
     "bf16_to_f32", "f32_to_f16_bits", "f16_bits_to_f32", "operand_as_f32", "config1_problem", "CONFIG1_TILES", "config2_shapes", "config2_split",
-    "config2_rows", "config2_extra_rows", "config3_shapes", "config4_shapes", "config5_shapes", "bf16_tuning_shapes",
+    "config2_rows", "config2_extra_rows", "config3_shapes", "config4_shapes", "config4_extra_rows", "config5_shapes", "bf16_tuning_shapes",
     "bf16_tuning_split",
 ]
 
@@ -244,6 +244,24 @@ def config4_shapes():
 
 CONFIG4_BATCH = 1024
 CONFIG4_ALPHA, CONFIG4_BETA = 1.0, 0.5
+
+
+def config4_extra_rows(n=240, seed=14):
+    """More batched small GEMMs for training the fp32 selector only: (M, N, K, batch) with every
+    dimension a multiple of 8 in [8, 64] and batch in {256, 512, 1024, 2048, 4096}; triples that
+    config 4 contains (all three dimensions powers of two) are left out, so its held-out shapes
+    stay unseen."""
+    r = np.random.default_rng(seed)
+    pow2 = {8, 16, 32, 64}
+    seen, out = set(), []
+    while len(out) < n:
+        M, N, K = (int(v) for v in 8 * r.integers(1, 9, size=3))
+        b = int(r.choice([256, 512, 1024, 2048, 4096]))
+        if ({M, N, K} <= pow2) or (M, N, K, b) in seen:
+            continue
+        seen.add((M, N, K, b))
+        out.append((M, N, K, b))
+    return out
 
 
 # --------------------------------------------------------------------------- config 5
