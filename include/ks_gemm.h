@@ -212,12 +212,14 @@ int ks_get_selector(int dtype, ks_tree_node_t *nodes, int cap);
  * the generic path (for testing it at aligned shapes); nonzero restores the default. */
 int ks_set_fast_path(int enabled);
 
-/* The large-tile fp32 32x32-MFMA members (LDS-staged, tile of at least 8192 entries and 128 columns, wave
- * tile of at most 2048, one K group) have a second form in which a work-group walks several consecutive tiles, requesting the next tile's operands before the
- * finished tile's C is stored; a one-dimensional launch without split-K does so with a count
- * chosen per call from the tile count and K.  n == 0 restores that default; 1 <= n <= 64 forces
- * the count (1 = every work-group one tile) for testing and tuning.  Results do not depend on it
- * (every tile is computed the same way whoever walks it).  Not thread-safe. */
+/* The large-tile fp32 32x32-MFMA members (LDS-staged, tile of at least 8192 entries and 128
+ * columns, wave tile of at most 2048, one K group) have a second form in which a work-group walks
+ * several consecutive tiles, requesting the next tile's operands before the finished tile's C is
+ * stored; a one-dimensional launch without split-K uses it with a count chosen per call from the
+ * tile count and K (only for very large outputs with at most two K-steps per tile).  n == 0
+ * restores that default; 1 <= n <= 64 forces the count (1 = every work-group one tile) for testing
+ * and tuning.  Results do not depend on it (every tile is computed the same way whoever walks it).
+ * Not thread-safe. */
 int ks_set_tiles_per_workgroup(int n);
 
 /* Measurement aid: copies `bytes` (a multiple of 16; both device pointers 16-byte aligned) with a
