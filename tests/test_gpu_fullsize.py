@@ -65,6 +65,7 @@ def test_config2_largest_and_random_rows(gpu):
 @pytest.mark.parametrize("shape", [
     (49, 32, 3), (196, 64, 27), (49, 2048, 4608), (3136, 128, 288), (25088, 512, 1152),
     (100352, 256, 576), (401408, 64, 27), (401408, 2048, 3),
+    (401408, 512, 27), (100352, 2048, 64),          # large outputs, short K: the multi-tile form
 ])
 def test_config3_im2col_shapes(gpu, shape):
     M, N, K = shape
