@@ -121,11 +121,18 @@ def fit_by_regime(Xtr, Ptr, n_single, n_batched, max_depth, min_samples_leaf, we
     return kept, join(r1, r2), join(t1, t2)
 
 
-def evaluate(tree, kept, X, P):
+def evaluate(tree, kept, X, P, flops=None):
+    """Scores of Section III-A / Table I on the rows given; with the rows' flop counts also the
+    ratio of summed times, best kernels over selected kernels (the geometric mean weighs every row
+    alike, the summed time is carried by the large ones)."""
     Ph = ks.tune_normalise(P)
     chosen = ks.tune_predict(tree, X)
-    return dict(achievable=ks.tune_achievable(Ph, kept), selector=ks.tune_selector_score(Ph, chosen),
-                best_single=max(ks.tune_achievable(Ph, [c]) for c in range(P.shape[1])))
+    out = dict(achievable=ks.tune_achievable(Ph, kept), selector=ks.tune_selector_score(Ph, chosen),
+               best_single=max(ks.tune_achievable(Ph, [c]) for c in range(P.shape[1])))
+    if flops is not None:
+        t = flops[:, None] / P
+        out["time_ratio"] = float(t.min(axis=1).sum() / t[np.arange(len(t)), chosen].sum())
+    return out
 
 
 def emit_table(trees):
@@ -184,6 +191,7 @@ def main(argv=None):
     T = np.concatenate(T, axis=0)
     P = perf_of(rows, T)
     X = features_of(rows, a.features)
+    F = np.array([2.0 * r["M"] * r["N"] * r["K"] * r["batch"] for r in rows])
     if a.all_rows:
         tr = te = np.ones(len(rows), dtype=bool)
     else:
@@ -199,12 +207,12 @@ def main(argv=None):
                                             a.weighted)
         else:
             kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted)
-        ev_tr, ev_te = evaluate(tree, kept, X[tr], P[tr]), evaluate(tree, kept, X[te], P[te])
+        ev_tr, ev_te = evaluate(tree, kept, X[tr], P[tr], F[tr]), evaluate(tree, kept, X[te], P[te], F[te])
         per_cfg = {}
         for cfg in sorted({r["config"] for r in rows}):
             m = te & np.array([r["config"] == cfg for r in rows])
             if m.any():
-                per_cfg[str(cfg)] = evaluate(tree, kept, X[m], P[m])
+                per_cfg[str(cfg)] = evaluate(tree, kept, X[m], P[m], F[m])
         report["sweep"].append(dict(n_kept=n, kept=kept.tolist(), tree_nodes=len(tree), train=ev_tr, test=ev_te,
                                     test_by_config=per_cfg))
         print("N=%2d kept=%-40s nodes=%3d | train achievable %.4f selector %.4f | test achievable %.4f "
@@ -212,8 +220,8 @@ def main(argv=None):
                                                     ev_tr["selector"], ev_te["achievable"],
                                                     ev_te["selector"], ev_te["best_single"]))
         if len(per_cfg) > 1:
-            print("      held-out by config: " + "  ".join("cfg%s: achievable %.4f selector %.4f" % (
-                c, v["achievable"], v["selector"]) for c, v in per_cfg.items()))
+            print("      held-out by config: " + "  ".join("cfg%s: achievable %.4f selector %.4f time %.4f" % (
+                c, v["achievable"], v["selector"], v["time_ratio"]) for c, v in per_cfg.items()))
         if n == a.n_kept:
             chosen_fit = (kept, reg, tree)
     kept, reg, tree = chosen_fit
