@@ -94,7 +94,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_f32_direct_ke
         for (int j = 0; j < FN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // register sets = K-steps in flight + the one being consumed; small sets afford more
-    constexpr int SET_REGS = 4 * NG * (FM + FN);
+    [[maybe_unused]] constexpr int SET_REGS = 4 * NG * (FM + FN);
     constexpr int S = KS_F32_DIRECT_SETS(SET_REGS);
     floatx4 a[S][NG][FM], b[S][NG][FN];
     // the lane's element at k = 0 of each fragment row / column, computed once
