@@ -172,7 +172,7 @@ def main():
     ap.add_argument("--dump-rows", default=None, help="write per-row kernel id, time and TFLOP/s as CSV")
     a = ap.parse_args()
     if a.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md); "
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path; "
                          "run with --gpus 1")
     import torch
     if not torch.cuda.is_available():

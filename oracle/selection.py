@@ -18,7 +18,7 @@ The deployed selector (Section IV) is a decision-tree classifier over the kept
 set, whose label for a training row is the kept configuration that is fastest
 there.  Scores (Section III-A and Table I) are geometric means over test rows.
 
-Readings where the paper is silent (all of them stated once more in the design doc):
+Readings where the paper is silent:
   * trees are CART: axis-aligned splits "x[f] <= t" go left; candidate thresholds
     are floor(midpoint) of consecutive distinct integer feature values, so the
     deployed selector compares integers only;
