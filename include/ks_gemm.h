@@ -170,6 +170,29 @@ int ks_gemm_out_bf16(int dtype, int kernel_id, int transA, int transB, int64_t M
                      float beta, uint16_t *C16, int64_t ldc, const float *bias,
                      int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): ks_gemm_*_with_kernel (kernel_id >= 0) or ks_gemm_*
+ * (kernel_id < 0: the deployed tree selects) with the split-K partial sums kept in a static device
+ * array of the library, KS_STATIC_SCRATCH_BYTES = 16 MiB per device (held by every device the
+ * library runs on until the process ends), instead of the registered workspace, which this call
+ * neither reads nor needs.  The call allocates and frees nothing.  dtype: type of A and B; A, B, C:
+ * device pointers as for ks_gemm_f32 / ks_gemm_bf16; the array's device address is looked up once
+ * per device on the first call there (the calling thread's current device).
+ *   - A forced member with a fixed split_k > 1 needs split_k * batch * M * N * 4 bytes: beyond
+ *     16 MiB the call returns KS_ERR_WORKSPACE and launches nothing.  Members with split_k == 0
+ *     take as many partitions as fit; with kernel_id < 0 a selected fixed-split member that does
+ *     not fit is replaced by its split_k == 1 twin, as in ks_gemm_*.
+ *   - Nothing has to start at zero: every partition writes its whole slice before the reduction
+ *     pass reads it, so the array may hold the previous call's contents.
+ *   - All calls on one device share that device's array: two such GEMMs that both split must not
+ *     be in flight together on one device (same stream, or ordered by the caller); overlapping
+ *     calls race. */
+#define KS_STATIC_SCRATCH_BYTES (16u << 20)
+int ks_gemm_static_scratch(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                           float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                           float beta, float *C, int64_t ldc,
+                           int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+
 /* Brute-force timing of one (workload, instantiation) cell (Section II-A: runtime recorded over a
  * number of iterations).  Runs `warmup` untimed launches, then `iters` samples; a sample is
  * `reps` back-to-back launches bracketed by one pair of HIP events on `stream`.  Synchronises and

@@ -53,7 +53,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
-    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
+    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
@@ -83,6 +83,7 @@ def lib():
     L.ks_gemm_bf16_with_kernel.argtypes = [_i] + _GEMM
     L.ks_gemm_bias.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
     L.ks_gemm_out_bf16.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
+    L.ks_gemm_static_scratch.argtypes = [_i, _i] + _GEMM
     L.ks_time_gemm.argtypes = [_i, _i] + _GEMM + [_i, _i, _i, _p]
     L.ks_num_kernels.argtypes = [_i]
     L.ks_kernel_info.argtypes = [_i, _i, ctypes.POINTER(KernelInfo)]
@@ -204,6 +205,14 @@ def gemm_out_bf16(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, l
                    strideB, strideC, stream)
     _check(lib().ks_gemm_out_bf16(int(dtype), int(kernel_id), *a[:13],
                                   _dev(bias) if bias is not None else None, *a[13:]), "ks_gemm_out_bf16")
+
+
+def gemm_static_scratch(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                        batch=1, strideA=0, strideB=0, strideC=0, stream=None):
+    """GEMM whose split-K scratch is the library's static device array; allocates nothing."""
+    _check(lib().ks_gemm_static_scratch(
+        int(dtype), int(kernel_id), *_gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                                                batch, strideA, strideB, strideC, stream)), "ks_gemm_static_scratch")
 
 
 def time_gemm(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,

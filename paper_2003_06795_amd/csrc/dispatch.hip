@@ -238,10 +238,17 @@ int validate(int transA, int transB, int64_t M, int64_t N, int64_t K, const void
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
-        const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
-        int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
-        const float *bias = nullptr, int out16 = 0) {
+// Scratch for split-K partial sums: the registered workspace, or the library's static array.
+struct Workspace {
+    void *ptr;
+    size_t bytes;
+};
+Workspace registered_ws() { return Workspace{g_ws, g_wsBytes}; }
+
+int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+           const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
+           int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
+           const float *bias = nullptr, int out16 = 0) {
     const InstanceDesc *d = desc_of(dtype, id);
     if (!d) return KS_ERR_INVALID_ARG;
     const int rc = validate(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, batch, strideC);
@@ -276,8 +283,8 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
         const int64_t steps = (kTiles + d->kw - 1) / d->kw;
         int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch, steps);
         const size_t per = (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
-        if (!g_ws) s = 1;
-        else if ((size_t)s * per > g_wsBytes) s = (int64_t)(g_wsBytes / per);
+        if (!wsp.ptr) s = 1;
+        else if ((size_t)s * per > wsp.bytes) s = (int64_t)(wsp.bytes / per);
         p.splitK = s < 1 ? 1 : (int)s;
     }
     p.kChunk = (int)(((kTiles + p.splitK - 1) / p.splitK) * d->bk);
@@ -300,8 +307,8 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
 
     if (p.splitK > 1) {
         const size_t need = (size_t)p.splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
-        if (!g_ws || g_wsBytes < need) return KS_ERR_WORKSPACE;
-        p.ws = static_cast<float *>(g_ws);
+        if (!wsp.ptr || wsp.bytes < need) return KS_ERR_WORKSPACE;
+        p.ws = static_cast<float *>(wsp.ptr);
     }
 
     // contiguous direction: A is K-contiguous when not transposed, B when transposed
@@ -341,6 +348,14 @@ int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t
         if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
     }
     return KS_OK;
+}
+
+int run(int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+        const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
+        int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
+        const float *bias = nullptr, int out16 = 0) {
+    return run_ws(registered_ws(), dtype, id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batch,
+                  strideA, strideB, strideC, stream, bias, out16);
 }
 
 }  // namespace
@@ -430,13 +445,14 @@ extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M,
 // Kernel for the selecting entry points: the tree's choice, unless that is a split-K instance and
 // the registered workspace cannot hold its partial sums; then the instance with the same tiles
 // and no split is used instead, so that a caller who never registers a workspace is still served.
-static int select_checked(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int tA, int tB) {
+static int select_checked(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int tA, int tB,
+                          Workspace w = registered_ws()) {
     const int id = ks_select(dtype, M, N, K, batch, tA, tB);
     if (id < 0) return id;
     const InstanceDesc *d = desc_of(dtype, id);
     if (!d || d->splitK <= 1 || M <= 0 || N <= 0 || batch <= 0) return id;
     const size_t need = (size_t)d->splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
-    if (g_ws && g_wsBytes >= need) return id;
+    if (w.ptr && w.bytes >= need) return id;
     const int n = dtype == KS_F32 ? kNumF32 : kNumBf16;
     for (int pass = 0; pass < 2; ++pass)          // same K-step first, then any K-step
         for (int i = 0; i < n; ++i) {
@@ -524,6 +540,52 @@ extern "C" int ks_gemm_out_bf16(int dtype, int kernel_id, int transA, int transB
     }
     float *C = reinterpret_cast<float *>(C16);        // element size is carried by the out16 flag
     return run(dtype, kernel_id, KS_GEMM_PASS, bias, 1);
+}
+
+// Entry point for callers that cannot allocate device memory (HIP graph capture, serving loops):
+// split-K partial sums go to a static device array instead of a registered workspace.
+#define KS_STATIC_SCRATCH_BYTES (16u << 20)
+namespace ks {
+namespace {
+__device__ __align__(256) float scratch[KS_STATIC_SCRATCH_BYTES / sizeof(float)];
+constexpr int kMaxDevices = 64;
+float *g_scratchPtr[kMaxDevices];      // device address of `scratch` on each device, once known
+std::mutex g_scratchMutex;
+
+// Device address of this device's copy of the static array (every device holds its own).  The
+// array's name is only a host-side handle: the address kernels can use comes from the runtime.
+int static_scratch(Workspace *out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KS_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratchMutex);
+    if (!g_scratchPtr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return KS_ERR_LAUNCH;
+        }
+        g_scratchPtr[dev] = static_cast<float *>(ptr);
+    }
+    out->ptr = g_scratchPtr[dev];
+    out->bytes = KS_STATIC_SCRATCH_BYTES;
+    return KS_OK;
+}
+}  // namespace
+}  // namespace ks
+
+extern "C" int ks_gemm_static_scratch(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                                      int64_t K, float alpha, const void *A, int64_t lda, const void *B,
+                                      int64_t ldb, float beta, float *C, int64_t ldc, int64_t batch,
+                                      int64_t strideA, int64_t strideB, int64_t strideC, void *stream) {
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
+    Workspace w{nullptr, 0};
+    const int rc = static_scratch(&w);
+    if (rc != KS_OK) return rc;
+    if (kernel_id < 0) {
+        kernel_id = select_checked(dtype, M, N, K, batch, transA, transB, w);
+        if (kernel_id < 0) return kernel_id;
+    }
+    return run_ws(w, dtype, kernel_id, KS_GEMM_PASS);
 }
 
 extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
