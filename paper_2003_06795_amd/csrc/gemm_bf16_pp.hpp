@@ -1,0 +1,351 @@
+// 256 x 256 x 64 member of the 16-bit family (paper Section II: one work-group tile, wave tile and
+// K-step of the templated kernel) in its "two groups of waves" form for gfx950.
+//
+// The eight waves of a work-group form two groups of four; a SIMD holds one wave of each group.
+// Every K-step is cut into four pairs of slots, a memory slot (LDS -> register fragment reads and
+// the issue of direct-to-LDS global loads) followed by a compute slot (eight 32x32x16 or sixteen
+// 16x16x32 MFMAs), each slot closed by s_barrier.  The second group runs one slot behind the
+// first, so on every SIMD one wave streams MFMAs while the other feeds the memory pipes.
+//
+// Tile decomposition: the 256 x 256 tile is four 128 x 128 quadrants (i, j); wave (wr, wc) of the
+// 2 x 4 wave grid owns the 64 x 32 block at rows wr*64, columns wc*32 of each quadrant.  The
+// operand tiles live in LDS as halves A0, A1 (rows 0..127 / 128..255 of the A tile) and B0, B1,
+// two stages each; a half is released as soon as the slot that consumes it has passed, and is
+// refilled at once with the K-step after next, so loads run about 1.5 K-steps ahead of their
+// use with two stages (128 KB) of LDS.
+//
+// Slots of K-step t (stage s = t & 1), per wave:
+//   M0  read A0, B0 fragments      issue A1(t+1) -> stage s^1        wait: B1(t) landed
+//   C0  quadrant (0,0)
+//   M1  read B1 fragments                                            wait: A1(t) landed
+//   C1  quadrant (0,1)
+//   M2  read A1 fragments          issue A0(t+2), B0(t+2) -> stage s
+//   C2  quadrant (1,1)
+//   M3                             issue B1(t+2) -> stage s          wait: A0(t+1), B0(t+1) landed
+//   C3  quadrant (1,0)
+// A wave waits (s_waitcnt vmcnt) for its own part of a half before the barrier that precedes the
+// slot in which any wave reads that half.  Preconditions are those of gemm_bf16_dma.hpp.
+#pragma once
+#include "gemm_bf16_dma.hpp"
+
+#ifndef KS_PP_SLOTS
+#define KS_PP_SLOTS 8
+#endif
+
+namespace ks {
+
+// Per-lane source offsets (bytes from the tile origin, row0 / col0 at this K-step) of the two
+// direct-to-LDS loads a wave contributes to one 128-row half of an operand tile.
+template <bool KC>
+struct PpPlan {
+    unsigned off[2];
+    __device__ __forceinline__ void init(int wave, int lane, long long ld, int row0, int half, int limit) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int L = (wave + j * 8) * 64 + lane;            // 16-byte slot in the LDS half
+            if constexpr (KC) {
+                const int r = L >> 3, pos = L & 7;
+                const int c = pos ^ ((r >> 1) & 7);
+                const int row = min(row0 + half * 128 + r, limit - 1) - row0;
+                off[j] = (unsigned)(((long long)row * ld + c * 8) * 2);
+            } else {
+                const int k = L >> 4, pos = L & 15;
+                const int c = pos ^ (2 * Bf16LdsT<128>::swz(k));
+                const int row = min(row0 + half * 128 + c * 8, limit - 8) - row0;
+                off[j] = (unsigned)(((long long)k * ld + row) * 2);
+            }
+        }
+    }
+    // tile: wave-uniform address of the tile origin at this K-step; lds: the LDS half (wave-uniform).
+    // Written as one instruction sequence so that the load keeps the form "scalar base + 32-bit
+    // lane offset" and so that the compiler, which cannot tell which LDS half an in-flight load
+    // fills once control flow merges, does not guard every LDS read with a full vmcnt wait: the
+    // waits for these loads are the explicit ones in the K loop.  M0 (the LDS destination) is
+    // written here and read by nothing else in this kernel.
+    __device__ __forceinline__ void issue(const char *tile, char *lds, int wave) const {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const unsigned dst = (unsigned)(uintptr_t)(lds_void_ptr)(lds + (wave + j * 8) * 1024);
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :
+                         : "v"(off[j]), "s"(tile), "s"(dst)
+                         : "memory");
+        }
+    }
+};
+
+template <int F, bool SPLIT, bool AKC, bool BKC, bool F16 = false>
+__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
+    constexpr int BM = 256, BN = 256, BK = 64, HALF = 128;
+    constexpr int FM = 64 / F, FN = 32 / F;                  // fragments of a wave's 64 x 32 block
+    constexpr int KSTEP = F == 32 ? 16 : 32, NSUB = BK / KSTEP;
+    constexpr int HB = HALF * BK * 2;                        // bytes of one half tile
+    // one LDS object per (operand, stage, half): in-flight loads into one never alias the reads of another
+    __shared__ __attribute__((aligned(1024))) char A00[HB];
+    __shared__ __attribute__((aligned(1024))) char A01[HB];
+    __shared__ __attribute__((aligned(1024))) char A10[HB];
+    __shared__ __attribute__((aligned(1024))) char A11[HB];
+    __shared__ __attribute__((aligned(1024))) char B00[HB];
+    __shared__ __attribute__((aligned(1024))) char B01[HB];
+    __shared__ __attribute__((aligned(1024))) char B10[HB];
+    __shared__ __attribute__((aligned(1024))) char B11[HB];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef KS_PP_TRACE
+    const unsigned long long clk0 = __builtin_amdgcn_s_memtime(), rt0 = __builtin_amdgcn_s_memrealtime();
+#endif
+    const int wr = wave >> 2, wc = wave & 3;
+    const TileCoord tc = tile_of_block(p);
+    const int row0 = tc.tm * BM, col0 = tc.tn * BN;
+    const int kBegin = tc.split * p.kChunk;
+    const int kEnd = min(p.K, kBegin + p.kChunk);
+    const int nk = (kEnd - kBegin) / BK;
+    const uint16_t *Ab = static_cast<const uint16_t *>(p.A) + (long long)tc.batch * p.strideA;
+    const uint16_t *Bb = static_cast<const uint16_t *>(p.B) + (long long)tc.batch * p.strideB;
+    float *Cb = p.C + (long long)tc.batch * p.strideC;
+    const char *aTile = reinterpret_cast<const char *>(AKC ? Ab + (long long)row0 * p.lda + kBegin
+                                                            : Ab + (long long)kBegin * p.lda + row0);
+    const char *bTile = reinterpret_cast<const char *>(BKC ? Bb + (long long)col0 * p.ldb + kBegin
+                                                            : Bb + (long long)kBegin * p.ldb + col0);
+    const long long aStep = AKC ? BK * 2LL : BK * 2LL * p.lda;
+    const long long bStep = BKC ? BK * 2LL : BK * 2LL * p.ldb;
+
+    PpPlan<AKC> pa0, pa1;
+    PpPlan<BKC> pb0, pb1;
+    pa0.init(wave, lane, p.lda, row0, 0, p.M);
+    pa1.init(wave, lane, p.lda, row0, 1, p.M);
+    pb0.init(wave, lane, p.ldb, col0, 0, p.N);
+    pb1.init(wave, lane, p.ldb, col0, 1, p.N);
+
+    // acc[i][j]: the wave's 64 x 32 block of quadrant (i, j)
+    floatx4 acc16[2][2][F == 16 ? FM : 1][F == 16 ? FN : 1];
+    floatx16 acc32[2][2][F == 32 ? FM : 1][F == 32 ? FN : 1];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int m = 0; m < FM; ++m)
+#pragma unroll
+            for (int n = 0; n < FN; ++n) {
+                if constexpr (F == 16) acc16[q >> 1][q & 1][m][n] = floatx4{0.f, 0.f, 0.f, 0.f};
+                else
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc32[q >> 1][q & 1][m][n][e] = 0.f;
+            }
+
+    bf16x8 a[FM][NSUB], b0[FN][NSUB], b1[FN][NSUB];
+
+    auto lds_a = [&](auto s, auto h) -> char * {
+        constexpr int S = decltype(s)::value, H = decltype(h)::value;
+        return S == 0 ? (H == 0 ? A00 : A01) : (H == 0 ? A10 : A11);
+    };
+    auto lds_b = [&](auto s, auto h) -> char * {
+        constexpr int S = decltype(s)::value, H = decltype(h)::value;
+        return S == 0 ? (H == 0 ? B00 : B01) : (H == 0 ? B10 : B11);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+
+    auto read_a = [&](const char *half) {
+#pragma unroll
+        for (int m = 0; m < FM; ++m)
+#pragma unroll
+            for (int ks = 0; ks < NSUB; ++ks)
+                a[m][ks] = read_fragment<F, HALF, BK, AKC>(half, wr * 64 + m * F, ks * KSTEP, lane);
+    };
+    auto read_b = [&](const char *half, bf16x8 (&b)[FN][NSUB]) {
+#pragma unroll
+        for (int n = 0; n < FN; ++n)
+#pragma unroll
+            for (int ks = 0; ks < NSUB; ++ks)
+                b[n][ks] = read_fragment<F, HALF, BK, BKC>(half, wc * 32 + n * F, ks * KSTEP, lane);
+    };
+    auto mma = [&](auto qi, auto qj, const bf16x8 (&b)[FN][NSUB]) {
+        constexpr int QI = decltype(qi)::value, QJ = decltype(qj)::value;
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < NSUB; ++ks)
+#pragma unroll
+            for (int m = 0; m < FM; ++m)
+#pragma unroll
+                for (int n = 0; n < FN; ++n) {
+                    if constexpr (F == 16)
+                        acc16[QI][QJ][m][n] = mfma_16x16x32<F16>(a[m][ks], b[n][ks], acc16[QI][QJ][m][n]);
+                    else
+                        acc32[QI][QJ][m][n] = mfma_32x32x16<F16>(a[m][ks], b[n][ks], acc32[QI][QJ][m][n]);
+                }
+        __builtin_amdgcn_s_setprio(0);
+    };
+    // end of a slot: nothing moves across it, then the work-group barrier
+    auto slot_end = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#ifdef KS_PP_TRACE
+    unsigned long long stamp[16];
+#define KS_PP_STAMP(i) stamp[i] = __builtin_amdgcn_s_memtime()
+#else
+#define KS_PP_STAMP(i)
+#endif
+
+#ifndef KS_PP_ABLATE
+#define KS_PP_ABLATE 0
+#endif
+#if KS_PP_ABLATE & 1
+#define KS_PP_IF_LOADS(x)
+#else
+#define KS_PP_IF_LOADS(x) x
+#endif
+#if KS_PP_ABLATE & 2
+#define KS_PP_IF_READS(x) if (t < 2) { x; }
+#else
+#define KS_PP_IF_READS(x) x
+#endif
+#if KS_PP_SLOTS == 4
+    // One K-step in two slot pairs.  Issue order of the loads: [A0 B0 B1](u) in M1(u-2), A1(u) in
+    // M0(u-1).  Every memory slot ends with its own LDS reads complete, so a half is free as soon as
+    // the barrier behind the second group's reading slot has been passed.
+    auto wait_lds = [&]() { __builtin_amdgcn_s_waitcnt(0xC07F); };      // lgkmcnt(0) only
+    auto step = [&](int t, auto s) {
+        constexpr int S = decltype(s)::value;
+        using SC = std::integral_constant<int, S>;
+        using SN = std::integral_constant<int, S ^ 1>;
+        const int t1 = min(t + 1, nk - 1), t2 = min(t + 2, nk - 1);
+        // M0
+        KS_PP_IF_READS(read_a(lds_a(SC{}, I0{})));
+        KS_PP_IF_READS(read_b(lds_b(SC{}, I0{}), b0));
+        KS_PP_IF_READS(read_b(lds_b(SC{}, I1{}), b1));
+        KS_PP_IF_LOADS(pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave));
+        wait_vmcnt<8>();                                     // A1(t) landed
+        wait_lds();
+        slot_end();
+        KS_PP_STAMP(S * 8 + 0);
+        mma(I0{}, I0{}, b0);
+        mma(I0{}, I1{}, b1);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 1);
+        // M1
+        KS_PP_IF_READS(read_a(lds_a(SC{}, I1{})));
+        KS_PP_IF_LOADS(pa0.issue(aTile + t2 * aStep, lds_a(SC{}, I0{}), wave));
+        KS_PP_IF_LOADS(pb0.issue(bTile + t2 * bStep, lds_b(SC{}, I0{}), wave));
+        KS_PP_IF_LOADS(pb1.issue(bTile + t2 * bStep, lds_b(SC{}, I1{}), wave));
+        wait_vmcnt<8>();                                     // A0, B0, B1 (t+1) landed
+        wait_lds();
+        slot_end();
+        KS_PP_STAMP(S * 8 + 2);
+        mma(I1{}, I1{}, b1);
+        mma(I1{}, I0{}, b0);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 3);
+    };
+#else
+    // One K-step.  Past the end of the K range the loads are issued all the same, on the last
+    // K-step's addresses and into halves nobody reads any more, so that every step is the same
+    // straight-line code and the waits can count on a fixed number of younger loads.
+    auto step = [&](int t, auto s) {
+        constexpr int S = decltype(s)::value;
+        using SC = std::integral_constant<int, S>;
+        using SN = std::integral_constant<int, S ^ 1>;
+        const int t1 = min(t + 1, nk - 1), t2 = min(t + 2, nk - 1);
+        // M0
+        read_a(lds_a(SC{}, I0{}));
+        read_b(lds_b(SC{}, I0{}), b0);
+        pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave);
+        wait_vmcnt<10>();
+        slot_end();
+        KS_PP_STAMP(S * 8 + 0);
+        mma(I0{}, I0{}, b0);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 1);
+        // M1
+        read_b(lds_b(SC{}, I1{}), b1);
+        wait_vmcnt<8>();
+        slot_end();
+        KS_PP_STAMP(S * 8 + 2);
+        mma(I0{}, I1{}, b1);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 3);
+        // M2
+        read_a(lds_a(SC{}, I1{}));
+        pa0.issue(aTile + t2 * aStep, lds_a(SC{}, I0{}), wave);
+        pb0.issue(bTile + t2 * bStep, lds_b(SC{}, I0{}), wave);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 4);
+        mma(I1{}, I1{}, b1);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 5);
+        // M3
+        pb1.issue(bTile + t2 * bStep, lds_b(SC{}, I1{}), wave);
+        wait_vmcnt<10>();
+        slot_end();
+        KS_PP_STAMP(S * 8 + 6);
+        mma(I1{}, I0{}, b0);
+        slot_end();
+        KS_PP_STAMP(S * 8 + 7);
+    };
+
+#endif
+
+    // A work-group whose K partition is empty (possible for the last split-K partition) only
+    // writes zeros; the branch is uniform over the work-group, so the barriers stay matched.
+    if (nk > 0) {
+        // prologue: K-steps 0 and 1 except A1(1), in the order the waits count on
+        const int s1 = min(1, nk - 1);
+        pa0.issue(aTile, lds_a(I0{}, I0{}), wave);
+        pb0.issue(bTile, lds_b(I0{}, I0{}), wave);
+        pb1.issue(bTile, lds_b(I0{}, I1{}), wave);
+        pa1.issue(aTile, lds_a(I0{}, I1{}), wave);
+        pa0.issue(aTile + s1 * aStep, lds_a(I1{}, I0{}), wave);
+        pb0.issue(bTile + s1 * bStep, lds_b(I1{}, I0{}), wave);
+        pb1.issue(bTile + s1 * bStep, lds_b(I1{}, I1{}), wave);
+#if KS_PP_SLOTS == 4
+        wait_vmcnt<8>();
+#else
+        wait_vmcnt<10>();
+#endif
+        slot_end();
+        if (wr == 1) slot_end();                             // the second group starts one slot later
+
+        int t = 0;
+#ifdef KS_PP_TRACE
+        const int nkLoop = nk - 6;      // stop early: the traced steps still prefetch real K-steps
+        for (; t + 2 <= nkLoop; t += 2) {
+#else
+        for (; t + 2 <= nk; t += 2) {
+#endif
+            step(t, I0{});
+            step(t + 1, I1{});
+        }
+#ifndef KS_PP_TRACE
+        if (t < nk) step(t, I0{});
+#endif
+        // the loads issued past the end must have landed before this work-group's LDS is given away
+        wait_vmcnt<0>();
+#ifdef KS_PP_TRACE
+        if (blockIdx.x < 64 && lane == 0) {
+            unsigned long long *tr = reinterpret_cast<unsigned long long *>(p.ws) + (blockIdx.x * 8 + wave) * 16;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tr[i] = stamp[i];
+            if (wave == 0) {
+                unsigned long long *c = reinterpret_cast<unsigned long long *>(p.ws) + 64 * 8 * 16 + blockIdx.x * 4;
+                c[0] = clk0; c[1] = rt0; c[2] = __builtin_amdgcn_s_memtime(); c[3] = __builtin_amdgcn_s_memrealtime();
+            }
+        }
+#endif
+        if (wr == 0) slot_end();                             // pairs with the second group's last slot
+    }
+
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int i = q >> 1, j = q & 1;
+        if constexpr (F == 16)
+            write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + i * HALF + wr * 64, col0 + j * HALF + wc * 32, lane,
+                                             acc16[i][j]);
+        else
+            write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + i * HALF + wr * 64, col0 + j * HALF + wc * 32, lane,
+                                             acc32[i][j]);
+    }
+}
+
+}  // namespace ks

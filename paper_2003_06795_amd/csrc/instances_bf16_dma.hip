@@ -1,5 +1,5 @@
 // One shard of the direct-to-LDS bf16 instantiations (see instances_f32.hip for the sharding scheme).
-#include "gemm_bf16_dma.hpp"
+#include "gemm_bf16_pp.hpp"
 #include "registry.hpp"
 
 #ifndef KS_SHARD
@@ -10,6 +10,11 @@
 
 namespace ks {
 
+// The eight-wave 256 x 256 x 64 members (128 x 64 of output per wave) run in the form with two
+// groups of waves alternating between memory and MFMA slots (gemm_bf16_pp.hpp).
+template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES>
+constexpr bool kTwoGroups = F == 32 && BM == 256 && BN == 256 && BK == 64 && WM == 128 && WN == 64 && STAGES == 2;
+
 // variant = akc * 2 + bkc
 template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT>
 static void launch_bf16_dma_fixed(const GemmParams &p, int grid, int variant, hipStream_t s) {
@@ -18,7 +23,10 @@ static void launch_bf16_dma_fixed(const GemmParams &p, int grid, int variant, hi
     // variant bit 4: the operands are IEEE binary16 instead of bf16
 #define KS_V(A, B)                                                                                                  \
     do {                                                                                                            \
-        if (variant & 16)                                                                                           \
+        if constexpr (kTwoGroups<F, BM, BN, BK, WM, WN, STAGES>) {                                                  \
+            if (variant & 16) hipLaunchKernelGGL((gemm_bf16_pp_kernel<F, SPLIT, A, B, true>), g, b, 0, s, p);       \
+            else hipLaunchKernelGGL((gemm_bf16_pp_kernel<F, SPLIT, A, B, false>), g, b, 0, s, p);                   \
+        } else if (variant & 16)                                                                                    \
             hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B, true>), g, b, 0, s, p);  \
         else                                                                                                        \
             hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B, false>), g, b, 0, s, p); \
