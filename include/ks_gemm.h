@@ -109,7 +109,7 @@ typedef struct {
  * the same tiles and split_k == 1 runs instead.  A, B, C: device pointers.
  * bf16 operands are raw bfloat16 bit patterns; accumulation and C are fp32.
  * Degenerate sizes: M, N or batch == 0 -> success, nothing launched; K == 0 -> C = beta*C.
- * Errors: KS_ERR_INVALID_ARG (see ks_status), KS_ERR_UNSUPPORTED when M, N or K >= 2^31 - 512,
+ * Errors: KS_ERR_INVALID_ARG (see ks_status), KS_ERR_UNSUPPORTED when M, N or K >= 2^31 - 512 or a leading dimension >= 2^31,
  * KS_ERR_WORKSPACE, KS_ERR_LAUNCH. */
 int ks_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
                 float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,

@@ -219,8 +219,9 @@ int validate(int transA, int transB, int64_t M, int64_t N, int64_t K, const void
     if (M < 0 || N < 0 || K < 0 || batch < 0) return KS_ERR_INVALID_ARG;
     const int64_t lim = 2147483647LL - 512;
     if (M >= lim || N >= lim || K >= lim || batch >= lim) return KS_ERR_UNSUPPORTED;
-    // leading dimensions take part in 64-bit element offsets (row * ld): keep the products far from overflow
-    const int64_t ldLim = 1LL << 40;
+    // leading dimensions take part in 64-bit element offsets (row * ld, row < 2^31): with ld < 2^31
+    // every such product stays below 2^62
+    const int64_t ldLim = 1LL << 31;
     if (lda >= ldLim || ldb >= ldLim || ldc >= ldLim) return KS_ERR_UNSUPPORTED;
     if (M == 0 || N == 0 || batch == 0) return KS_OK;
     if (!C || ldc < N) return KS_ERR_INVALID_ARG;
@@ -229,7 +230,9 @@ int validate(int transA, int transB, int64_t M, int64_t N, int64_t K, const void
         if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return KS_ERR_INVALID_ARG;
     }
     if (batch > 1) {
-        const int64_t span = (M - 1) * ldc + N;       // elements one item of C covers
+        int64_t span = 0;                             // elements one item of C covers
+        if (__builtin_mul_overflow(M - 1, ldc, &span) || __builtin_add_overflow(span, N, &span))
+            return KS_ERR_UNSUPPORTED;
         const int64_t s = strideC < 0 ? -strideC : strideC;
         if (s < span) return KS_ERR_INVALID_ARG;
     }

@@ -137,3 +137,20 @@ def test_workspace_bytes():
             assert got % (2 * 100 * 50 * 4) == 0 and got <= 64 * 2 * 100 * 50 * 4
         else:
             assert got == (0 if ki["split_k"] == 1 else ki["split_k"] * 2 * 100 * 50 * 4)
+
+
+def test_sizes_beyond_the_offset_arithmetic_are_refused_before_any_launch():
+    """Leading dimensions of 2^31 or more, or dimensions near 2^31, return the unsupported status from
+    the host-side checks (no device is touched, so this also holds on a box without a GPU); just
+    below the limits the call gets past the checks (and, without a device, fails later)."""
+    dummy = 4096                                     # never dereferenced: the checks come first
+    L = ks.lib()
+    def call(M, N, K, lda, ldb, ldc, batch=1, strideC=0):
+        return L.ks_gemm_f32_with_kernel(0, 0, 0, M, N, K, 1.0, dummy, lda, dummy, ldb, 0.0, dummy, ldc,
+                                         batch, 0, 0, strideC, None)
+    assert call(8, 8, 8, 2 ** 31, 8, 8) == ks.ERR_UNSUPPORTED
+    assert call(8, 8, 8, 8, 2 ** 31, 8) == ks.ERR_UNSUPPORTED
+    assert call(8, 8, 8, 8, 8, 2 ** 31) == ks.ERR_UNSUPPORTED
+    assert call(2 ** 31 - 512, 8, 8, 8, 8, 8) == ks.ERR_UNSUPPORTED
+    # (M - 1) * ldc + N stays below 2^62: the overlap test sees the true span and refuses
+    assert call(2 ** 31 - 600, 8, 8, 8, 8, 2 ** 31 - 1, batch=2, strideC=2 ** 40) == ks.ERR_INVALID_ARG
