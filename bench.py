@@ -1,18 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg5] [--single-launch]
 
 A step is one pass of the deployed library over the workload: for every (shape, layout) row,
 ks_select picks a kernel and ks_gemm_* runs it (inputs resident in HBM).  The default workload is
 the fp32 tuning set (200 log-uniform shapes x 4 layouts = 800 GEMMs); `value` is the geometric
 mean over rows of TFLOP/s, each row's time being the median over the K timed steps of the HIP
-event interval around its launch.  One JSON line is printed with the roofline of the dominant
-kernel and the CPU oracle timed on a bounded sample of the same rows.
+event interval around its launch.  One JSON line is printed.  Besides the contract's fields it
+carries, all measured in the same run after the timed region:
+  roofline       the single-kernel GEMM symbol with the most device time in a pass
+  selector       stored held-out score and a live one: every kernel timed on seeded held-out rows
+  fp32_large     4096^3 in four layouts and three large im2col rows, fraction of the fp32 matrix peak
+  cfg3_sample, cfg4   geometric means over an im2col sample and the 64 batched small shapes
+  bf16_large     the large / skinny bf16 cells, fraction of the bf16 matrix peak and of what a pure
+                 MFMA loop sustains on the same operand values (ks_mfma_sustained)
+  cpu_baseline   the CPU oracle on a bounded sample of the same rows
+--single-launch makes every sample one launch (what a profiler run wants: each row then
+contributes the same number of launches to its kernel symbol's average).
 """
 import argparse
 import json
 import os
+import platform
 import sys
 import time
 
@@ -23,6 +33,8 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"f32": 157.3, "bf16": 2516.6}      # dense matrix-core TFLOP/s of MI355X
 HBM_TBS = 8.0                              # published HBM3E bandwidth, TB/s
+CALIB_BYTES = 256 * 1024 * 1024
+SAMPLES = 3                                 # timed samples per row per step
 
 
 def attainable_tflops(dtype, M, N, K, batch=1, beta=0.0):
@@ -31,17 +43,14 @@ def attainable_tflops(dtype, M, N, K, batch=1, beta=0.0):
     esz = 4 if dtype == "f32" else 2
     by = batch * ((M * K + K * N) * esz + M * N * 4 * (2 if beta != 0.0 else 1))
     return min(PEAK[dtype], 2.0 * M * N * K * batch / by * HBM_TBS)
-HBM_PEAK_GBS = 8000.0
-CALIB_BYTES = 256 * 1024 * 1024
-SAMPLES = 3                                 # timed samples per row per step
 
 
-def kernel_symbol(ks, dt, kid, tA, tB, vec=True, dma=False):
-    """Name of the device function a call resolves to (as rocprofv3 prints it).  dma: the bf16
-    direct-to-LDS path applies (aligned operands and K a multiple of the K-step)."""
-    ki = ks.kernel_info(dt, kid)
+def kernel_symbol(ks, dt, plan, tA, tB):
+    """Name of the device function a call resolves to (as rocprofv3 prints it), from what the
+    library says it would launch (ks_gemm_plan): member, split actually taken, code path."""
+    ki = ks.kernel_info(dt, plan["kernel_id"])
     akc, bkc = int(not tA), int(bool(tB))
-    split = ki["split_k"] > 1
+    split, vec = plan["split_k"] > 1, plan["vector_loads"]
     b = lambda v: "true" if v else "false"
     if dt == ks.F32 and ki["core_name"] == "direct":
         return "gemm_f32_direct_kernel<%d, %d, %d, %d, %d, %s, %s, %s, %s>" % (
@@ -51,11 +60,13 @@ def kernel_symbol(ks, dt, kid, tA, tB, vec=True, dma=False):
             ki["bm"], ki["bn"], ki["bk"], ki["k_waves"], ki["wm"], b(split), b(akc), b(bkc), b(vec))
     if dt == ks.F32:
         p1, p2 = (ki["tm"], ki["tn"]) if ki["core_name"] == "fma" else (ki["wm"], ki["wn"])
-        # last argument: the multi-tile form, which no row of the benchmark's workloads is large enough for
-        return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s, %d, false>" % (
-            ki["core"], ki["bm"], ki["bn"], ki["bk"], p1, p2, b(split), b(akc), b(bkc), b(vec), ki["k_waves"])
+        return "gemm_f32_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s, %d, %s>" % (
+            ki["core"], ki["bm"], ki["bn"], ki["bk"], p1, p2, b(split), b(akc), b(bkc), b(vec), ki["k_waves"],
+            b(plan["tiles_per_workgroup"] > 1))
     f = 16 if ki["core_name"] == "mfma16" else 32
-    if vec and dma:
+    if plan["path"] == 2:
+        return "gemm_bf16_pp_kernel<%d, %s, %s, %s, false>" % (f, b(split), b(akc), b(bkc))
+    if plan["path"] == 1:
         stages = ki["lds_bytes"] // (ki["bk"] * (ki["bm"] + ki["bn"]) * 2)
         return "gemm_bf16_dma_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %s, false>" % (
             f, ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], stages, b(split), b(akc), b(bkc))
@@ -73,6 +84,23 @@ def build_rows(workload):
         for s, (M, N, K) in enumerate(wl.config5_shapes()):
             for (tA, tB) in wl.CONFIG5_LAYOUTS:
                 rows.append(dict(dtype="bf16", shape=s, tA=tA, tB=tB, M=M, N=N, K=K, batch=1, alpha=1.0, beta=0.0))
+    elif workload == "cfg4":
+        for s, (M, N, K) in enumerate(wl.config4_shapes()):
+            rows.append(dict(dtype="f32", shape=s, tA=0, tB=0, M=M, N=N, K=K, batch=wl.CONFIG4_BATCH,
+                             alpha=wl.CONFIG4_ALPHA, beta=wl.CONFIG4_BETA))
+    elif workload == "cfg3_sample":
+        shapes = wl.config3_shapes()
+        pick = np.random.default_rng(3).choice(len(shapes), 64, replace=False)
+        for s in sorted(int(i) for i in pick):
+            M, N, K = shapes[s]
+            if (M * K + K * N + M * N) * 4 > 6e9:          # keeps the sample's footprint bounded
+                continue
+            rows.append(dict(dtype="f32", shape=s, tA=0, tB=0, M=M, N=N, K=K, batch=1, alpha=1.0, beta=0.0))
+    elif workload == "fp32_large":
+        for s, (M, N, K) in enumerate([(4096, 4096, 4096), (100352, 2048, 4608), (25088, 512, 1152),
+                                       (401408, 2048, 32)]):
+            for (tA, tB) in (((0, 0), (0, 1), (1, 0), (1, 1)) if s == 0 else ((0, 0),)):
+                rows.append(dict(dtype="f32", shape=s, tA=tA, tB=tB, M=M, N=N, K=K, batch=1, alpha=1.0, beta=0.0))
     else:
         raise SystemExit("unknown workload %r" % workload)
     return rows
@@ -95,26 +123,59 @@ def allocate(rows, torch):
             s = 1.0 / np.sqrt(K)
             A = (torch.randn(M * K * b, generator=g, device="cuda") * s).to(torch.bfloat16)
             B = (torch.randn(K * N * b, generator=g, device="cuda") * s).to(torch.bfloat16)
-        C = torch.zeros(M * N * b, device="cuda")
+        C = (torch.rand(M * N * b, generator=g, device="cuda") * 2 - 1) if r["beta"] != 0.0 else \
+            torch.zeros(M * N * b, device="cuda")
         bufs[key] = (A, B, C)
     return bufs
 
 
-def run_pass(ks, rows, bufs, reps, stream, out_ms=None):
+def gemm_args(r, bufs):
+    A, B, C = bufs[(r["dtype"], r["shape"])]
+    M, N, K, b = r["M"], r["N"], r["K"], r["batch"]
+    return (r["tA"], r["tB"], M, N, K, r["alpha"], A, M if r["tA"] else K, B, K if r["tB"] else N, r["beta"], C, N,
+            b, M * K if b > 1 else 0, K * N if b > 1 else 0, M * N if b > 1 else 0)
+
+
+def reps_of(rows, single):
+    """Launches per sample: about 1.2e9 flops, at most 64 (roughly the tuner's 100 us samples), a
+    fixed function of the row so that warm-up and timed passes launch exactly the same kernels."""
+    if single:
+        return [1] * len(rows)
+    return [int(min(64, max(1, np.ceil(1.2e9 / (2.0 * r["M"] * r["N"] * r["K"] * r["batch"]))))) for r in rows]
+
+
+def run_pass(ks, rows, bufs, reps, stream, out_ms=None, kernel=-1):
     """One pass: every row's GEMM with the selected kernel (kernel id -1 = ks_select), timed the way
     the tuner times a cell (ks_time_gemm): one untimed launch, then SAMPLES samples of reps[i]
     back-to-back launches, each between one HIP event pair.  The untimed launch keeps the queue
     ahead of the device, so a sample measures kernel time and not the host's enqueue rate.
     out_ms[i] receives the median per-launch milliseconds of the samples."""
     for i, r in enumerate(rows):
-        A, B, C = bufs[(r["dtype"], r["shape"])]
-        M, N, K, b = r["M"], r["N"], r["K"], r["batch"]
-        ms = ks.time_gemm(ks.F32 if r["dtype"] == "f32" else ks.BF16, -1, r["tA"], r["tB"], M, N, K,
-                          r["alpha"], A, M if r["tA"] else K, B, K if r["tB"] else N, r["beta"], C, N, b,
-                          M * K if b > 1 else 0, K * N if b > 1 else 0, M * N if b > 1 else 0,
+        ms = ks.time_gemm(ks.F32 if r["dtype"] == "f32" else ks.BF16, kernel, *gemm_args(r, bufs),
                           stream=stream, warmup=1, iters=SAMPLES, reps=reps[i])
         if out_ms is not None:
             out_ms[i] = float(np.median(ms))
+
+
+def ensure_workspace(ks, torch, nbytes, _state={}):
+    if nbytes > _state.get("bytes", 0):
+        _state["buf"] = torch.empty(nbytes // 4 + 1, dtype=torch.float32, device="cuda")
+        _state["bytes"] = nbytes
+    if "buf" in _state:
+        ks.set_workspace(_state["buf"])
+
+
+def workspace_for(ks, torch, rows):
+    need = 0
+    for r in rows:
+        dt = ks.F32 if r["dtype"] == "f32" else ks.BF16
+        kid = ks.select(dt, r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"])
+        need = max(need, ks.workspace_bytes_needed(dt, kid, r["M"], r["N"], r["batch"]))
+    ensure_workspace(ks, torch, need)
+
+
+def flops_of(rows):
+    return np.array([2.0 * r["M"] * r["N"] * r["K"] * r["batch"] for r in rows])
 
 
 def stored_traffic(workload, symbol):
@@ -130,18 +191,27 @@ def stored_traffic(workload, symbol):
     return None
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return platform.processor() or "unknown"
+
+
 def cpu_baseline(rows, budget_s=12.0):
     """The CPU oracle, as it stands, on a seeded sample of the same rows (small ones first so the
-    sample is bounded); reports the geometric mean of its TFLOP/s over the sampled rows."""
+    sample is bounded); geometric mean of its TFLOP/s over the sampled rows with all the threads
+    OpenMP gives it, and again on the first rows of the sample with one thread."""
     import workloads as wl
     from oracle import gemm as og
     order = np.random.default_rng(0).permutation(len(rows))
-    picked, rates, spent = [], [], 0.0
-    for i in order:
+    threads = og.num_threads()
+
+    def timed(i):
         r = rows[int(i)]
-        macs = r["M"] * r["N"] * r["K"] * r["batch"]
-        if macs > 2 ** 34 or spent > budget_s:
-            continue
         p = wl.make_problem(r["dtype"], r["tA"], r["tB"], r["M"], r["N"], r["K"], batch=r["batch"],
                             alpha=r["alpha"], beta=r["beta"], seed=1, key=int(i),
                             dist="normal" if r["dtype"] == "bf16" else "uniform")
@@ -149,16 +219,138 @@ def cpu_baseline(rows, budget_s=12.0):
         t0 = time.perf_counter()
         og.gemm(p.dtype, p.transA, p.transB, p.M, p.N, p.K, p.alpha, p.A, p.lda, p.B, p.ldb, p.beta, C,
                 p.ldc, p.batch, p.strideA, p.strideB, p.strideC)
-        dt = time.perf_counter() - t0
+        return time.perf_counter() - t0
+
+    picked, rates, spent = [], [], 0.0
+    for i in order:
+        r = rows[int(i)]
+        macs = r["M"] * r["N"] * r["K"] * r["batch"]
+        if macs > 2 ** 34 or spent > budget_s:
+            continue
+        dt = timed(i)
         spent += dt
         picked.append(int(i))
         rates.append(2.0 * macs / dt / 1e12)
         if len(picked) >= 400:
             break
-    return dict(value=float(np.exp(np.mean(np.log(rates)))), unit="TFLOP/s (geomean over sampled rows)",
-                cores=og.num_threads(), kind="oracle",
+    # one thread: the same rows in the same order until a third of the budget is spent
+    og.set_num_threads(1)
+    rates1, spent1 = [], 0.0
+    try:
+        for i in picked:
+            r = rows[i]
+            macs = r["M"] * r["N"] * r["K"] * r["batch"]
+            if macs > 2 ** 30 or spent1 > budget_s / 3:
+                continue
+            dt = timed(i)
+            spent1 += dt
+            rates1.append(2.0 * macs / dt / 1e12)
+    finally:
+        og.set_num_threads(threads)
+    gm = lambda v: float(np.exp(np.mean(np.log(v)))) if len(v) else None
+    return dict(value=gm(rates), unit="TFLOP/s (geomean over sampled rows)", cores=threads, kind="oracle",
+                cpu=cpu_model(),
                 sample="%d seeded rows of the workload with M*N*K <= 2^34, full fp64 triple loop, %.1f s of CPU work"
-                       % (len(picked), spent))
+                       % (len(picked), spent),
+                one_thread=dict(value=gm(rates1), cores=1,
+                                sample="%d of those rows with M*N*K <= 2^30, %.1f s" % (len(rates1), spent1)))
+
+
+def frac_summary(tflops, rows):
+    """Achieved / min(peak, AI x 8 TB/s) per row: geometric mean, quartiles and the maximum.  Most rows
+    of the fp32 tuning set last a few microseconds, where launch latency (not in this bound) rules."""
+    f = np.array([t / attainable_tflops(r["dtype"], r["M"], r["N"], r["K"], r["batch"], r["beta"])
+                  for t, r in zip(tflops, rows)])
+    q = np.quantile(f, [0.25, 0.5, 0.75])
+    return dict(geomean=float(np.exp(np.mean(np.log(f)))), q25=float(q[0]), median=float(q[1]),
+                q75=float(q[2]), max=float(f.max()))
+
+
+def time_set(ks, torch, workload, iters=10):
+    """Selected kernels on a named shape set, after the timed region: per-cell TFLOP/s."""
+    rows = build_rows(workload)
+    cells = []
+    # one shape at a time: the large im2col rows hold several GB
+    for key in sorted({r["shape"] for r in rows}):
+        sub = [r for r in rows if r["shape"] == key]
+        bufs = allocate(sub, torch)
+        workspace_for(ks, torch, sub)
+        for r in sub:
+            dt = ks.F32 if r["dtype"] == "f32" else ks.BF16
+            args = gemm_args(r, bufs)
+            plan = ks.gemm_plan(dt, -1, *args)
+            fl = 2.0 * r["M"] * r["N"] * r["K"] * r["batch"]
+            reps = int(min(64, max(1, np.ceil(1.2e9 / fl))))
+            t = float(np.median(ks.time_gemm(dt, -1, *args, warmup=2, iters=iters, reps=reps)))
+            tf = fl / (t * 1e-3) / 1e12
+            att = attainable_tflops(r["dtype"], r["M"], r["N"], r["K"], r["batch"], r["beta"])
+            cells.append(dict(M=r["M"], N=r["N"], K=r["K"], batch=r["batch"], layout="NT"[r["tA"]] + "NT"[r["tB"]],
+                              kernel=plan["kernel_id"], split_k=plan["split_k"], ms=t, tflops=tf,
+                              frac_of_peak=tf / PEAK[r["dtype"]], attainable_tflops=att, frac_of_attainable=tf / att))
+        del bufs
+        torch.cuda.empty_cache()
+    return cells
+
+
+def geomean(v):
+    return float(np.exp(np.mean(np.log(np.asarray(v, dtype=np.float64)))))
+
+
+def selector_live(ks, torch, n_shapes=6):
+    """Section III-A / Table I measured in this run: every one of the 64 fp32 kernels timed on seeded
+    held-out rows of the tuning set (shapes the deployed tree never saw), and the geometric mean of
+    time(best kernel) / time(selected kernel)."""
+    import workloads as wl
+    held = wl.config2_split()[1]
+    pick = sorted(int(s) for s in np.random.default_rng(7).choice(held, n_shapes, replace=False))
+    rows = [r for r in build_rows("cfg2") if r["shape"] in pick]
+    bufs = allocate(rows, torch)
+    nk = ks.num_kernels(ks.F32)
+    need = 0
+    for r in rows:
+        for k in range(nk):
+            need = max(need, ks.workspace_bytes_needed(ks.F32, k, r["M"], r["N"], r["batch"]))
+    ensure_workspace(ks, torch, min(need, 1 << 30))
+    reps = reps_of(rows, False)
+    ratios, detail = [], []
+    for i, r in enumerate(rows):
+        args = gemm_args(r, bufs)
+        sel = ks.gemm_plan(ks.F32, -1, *args)["kernel_id"]
+        t = np.full(nk, np.inf)
+        for k in range(nk):
+            try:
+                t[k] = float(np.median(ks.time_gemm(ks.F32, k, *args, warmup=1, iters=SAMPLES, reps=reps[i])))
+            except ks.KsError:
+                pass                                  # a fixed-split member beyond the workspace
+        best = int(np.argmin(t))
+        ratios.append(t[best] / t[sel])
+        detail.append(dict(M=r["M"], N=r["N"], K=r["K"], layout="NT"[r["tA"]] + "NT"[r["tB"]], selected=sel,
+                           best=best, ratio=float(t[best] / t[sel])))
+    return dict(rows=len(rows), kernels_timed=nk, held_out_shapes=pick,
+                selected_over_best_geomean=geomean(ratios), worst=min(detail, key=lambda d: d["ratio"]))
+
+
+def bf16_report(ks, torch):
+    """Selected bf16 kernels on the large/skinny set: TFLOP/s, fraction of the bf16 matrix peak, and
+    fraction of what a pure MFMA loop sustains on the same operand values in this run."""
+    cells = time_set(ks, torch, "cfg5")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1000)
+    ops = (torch.randn(ks.MFMA_PROBE_BYTES // 2, generator=g, device="cuda") / np.sqrt(8192.0)).to(torch.bfloat16)
+    sustained, mhz = ks.mfma_sustained(ks.BF16, ops, rounds=4000)
+    zeros = torch.zeros(ks.MFMA_PROBE_BYTES // 2, dtype=torch.bfloat16, device="cuda")
+    sustained0, mhz0 = ks.mfma_sustained(ks.BF16, zeros, rounds=4000)
+    for c in cells:
+        c["frac_of_sustained_mfma"] = c["tflops"] / sustained
+    big = [c for c in cells if min(c["M"], c["N"]) >= 2048]
+    return dict(cells=cells, geomean_tflops=geomean([c["tflops"] for c in cells]),
+                best_frac_of_peak=max(c["frac_of_peak"] for c in big),
+                best_frac_of_sustained_mfma=max(c["frac_of_sustained_mfma"] for c in big),
+                mfma_sustained=dict(what="ks_mfma_sustained: 2048 work-groups x 8 waves of 32x32x16 bf16 MFMAs on "
+                                         "register operands, no LDS or memory traffic",
+                                    normal_operands=dict(tflops=sustained, shader_mhz=mhz,
+                                                         values="N(0,1)/sqrt(8192) rounded to bf16, as the cells use"),
+                                    zero_operands=dict(tflops=sustained0, shader_mhz=mhz0)))
 
 
 def main():
@@ -167,8 +359,9 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
+    ap.add_argument("--single-launch", action="store_true", help="one launch per sample (profiler runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the bf16 large-shape report")
+    ap.add_argument("--no-extra", action="store_true", help="skip the reports measured after the timed region")
     ap.add_argument("--dump-rows", default=None, help="write per-row kernel id, time and TFLOP/s as CSV")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -189,19 +382,9 @@ def main():
     dtype = rows[0]["dtype"]
     dt = ks.F32 if dtype == "f32" else ks.BF16
     bufs = allocate(rows, torch)
-    need = max(ks.workspace_bytes_needed(dt, ks.select(dt, r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"]),
-                                         r["M"], r["N"], r["batch"]) for r in rows)
-    ws = None
-    if need:
-        ws = torch.empty(need // 4 + 1, dtype=torch.float32, device="cuda")
-        ks.set_workspace(ws)
+    workspace_for(ks, torch, rows)
 
-    # Like the tuner, a row's sample is a short run of back-to-back launches (issued natively by
-    # ks_time_gemm) so that the event interval measures kernel time rather than host dispatch.  The
-    # repetition count is a fixed function of the row's flops (about 1.2e9 flops per sample, at
-    # most 64 launches: roughly the tuner's 100 us samples), so warm-up and timed passes launch
-    # exactly the same kernels.
-    reps = [int(min(64, max(1, np.ceil(1.2e9 / (2.0 * r["M"] * r["N"] * r["K"] * r["batch"]))))) for r in rows]
+    reps = reps_of(rows, a.single_launch)
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(a.warmup):
         run_pass(ks, rows, bufs, reps, stream)
@@ -214,39 +397,39 @@ def main():
     wall = time.perf_counter() - t0
 
     med = np.median(ms, axis=0)
-    flops = np.array([2.0 * r["M"] * r["N"] * r["K"] * r["batch"] for r in rows])
+    flops = flops_of(rows)
     tflops = flops / (med * 1e-3) / 1e12
-    value = float(np.exp(np.mean(np.log(tflops))))
+    value = geomean(tflops)
 
-    # dominant kernel symbol: the instantiation with the most device time in a step
-    chosen = [ks.select(dt, r["M"], r["N"], r["K"], r["batch"], r["tA"], r["tB"]) for r in rows]
+    # what each row launched, from the library itself (same workspace as in the timed region)
+    plans = [ks.gemm_plan(dt, -1, *gemm_args(r, bufs)) for r in rows]
+    chosen = [p["kernel_id"] for p in plans]
     if a.dump_rows:
         with open(a.dump_rows, "w") as f:
-            f.write("row,transA,transB,M,N,K,kernel,reps,median_ms,tflops\n")
+            f.write("row,transA,transB,M,N,K,kernel,split_k,reps,median_ms,tflops\n")
             for i, r in enumerate(rows):
-                f.write("%d,%d,%d,%d,%d,%d,%d,%d,%.6g,%.6g\n" % (i, r["tA"], r["tB"], r["M"], r["N"], r["K"],
-                                                               chosen[i], reps[i], med[i], tflops[i]))
-    sym = [kernel_symbol(ks, dt, k, r["tA"], r["tB"], vec=all(v % 8 == 0 for v in (r["M"], r["N"], r["K"])),
-                         dma=dtype == "bf16" and r["K"] % ks.kernel_info(dt, k)["bk"] == 0)
-           for k, r in zip(chosen, rows)]
+                f.write("%d,%d,%d,%d,%d,%d,%d,%d,%d,%.6g,%.6g\n" % (i, r["tA"], r["tB"], r["M"], r["N"], r["K"],
+                                                                  chosen[i], plans[i]["split_k"], reps[i], med[i],
+                                                                  tflops[i]))
+    sym = [kernel_symbol(ks, dt, p, r["tA"], r["tB"]) for p, r in zip(plans, rows)]
     # Per kernel symbol: `pass_*` counts every row once (one pass of the workload = one GEMM per
     # row); `all_*` counts every timed launch (rows of few flops are repeated up to 64 times per
     # sample, a measurement device), which is what a profiler's per-symbol average sees.
     by = {}
+    esz = 4 if dtype == "f32" else 2
     for i, s in enumerate(sym):
         d = by.setdefault(s, dict(pass_time=0.0, pass_flops=0.0, pass_bytes=0.0, rows=0, all_time=0.0,
-                                  all_launches=0, split=ks.kernel_info(dt, chosen[i])["split_k"] > 1))
+                                  all_launches=0, split=plans[i]["split_k"] > 1))
         r = rows[i]
-        esz = 4 if dtype == "f32" else 2
         d["pass_time"] += float(med[i]) * 1e-3
         d["pass_flops"] += float(flops[i])
         d["pass_bytes"] += r["batch"] * ((r["M"] * r["K"] + r["K"] * r["N"]) * esz + r["M"] * r["N"] * 4)
         d["rows"] += 1
         d["all_time"] += float(ms[:, i].sum()) * 1e-3 * SAMPLES * reps[i]
         d["all_launches"] += a.steps * SAMPLES * reps[i]
-    # A split-K GEMM is two kernels (partial products, then the fixed-order reduction) inside one
-    # timed interval, so its interval is not one kernel's duration; the roofline is taken for the
-    # symbol with the most time in a pass among the single-kernel GEMMs.
+    # A GEMM that splits K is two kernels (partial products, then the fixed-order reduction) inside
+    # one timed interval, so its interval is not one kernel's duration; the roofline is taken for
+    # the symbol with the most time in a pass among the rows that run a single kernel.
     single = [s_ for s_ in by if not by[s_]["split"]]
     dom = max(single or list(by), key=lambda s_: by[s_]["pass_time"])
     d = by[dom]
@@ -254,12 +437,16 @@ def main():
     traffic = stored_traffic(a.workload, dom)
     if traffic is not None:
         traffic["algorithmic_bytes"] = d["pass_bytes"] / d["rows"]
+    pass_time = float(med.sum() * 1e-3)
     roofline = dict(bound="mfma", kernel=dom, achieved=achieved, peak=PEAK[dtype], unit="TFLOP/s",
                     frac=achieved / PEAK[dtype], traffic=traffic, launches_per_pass=d["rows"],
+                    flops_per_launch=d["pass_flops"] / d["rows"],
                     avg_launch_us=d["pass_time"] / d["rows"] * 1e6,
                     avg_launch_us_over_all_timed_launches=d["all_time"] / d["all_launches"] * 1e6,
-                    share_of_pass_time=d["pass_time"] / float(med.sum() * 1e-3),
-                    algorithmic_gbs=d["pass_bytes"] / d["pass_time"] / 1e9)
+                    share_of_pass_time=d["pass_time"] / pass_time,
+                    algorithmic_gbs=d["pass_bytes"] / d["pass_time"] / 1e9,
+                    how=("achieved = flops_per_launch / avg_launch_us (HIP events, mean over the rows that "
+                         "resolve to this symbol); rows whose GEMM splits K are other symbols"))
 
     out = {
         "metric": "GEMM TFLOP/s geomean over shape set; selected/exhaustive-best perf ratio",
@@ -270,15 +457,19 @@ def main():
                                 "selected kernel per row" if a.workload == "cfg2" else
                                 "bf16 large/skinny set: 7 shapes x {NN,NT}, selected kernel per row"),
                    "rows": len(rows), "kernels_used": len(set(chosen)),
+                   "rows_that_split_k": int(sum(p["split_k"] > 1 for p in plans)),
                    "launches_per_step": int(sum(1 + SAMPLES * r for r in reps)),
                    "timing": ("per row and step: ks_time_gemm with 1 untimed launch and %d samples of `reps` back-to-back "
                               "launches between HIP events; row time = median over steps of the per-step median" % SAMPLES)},
         "timed_device_ms_per_step": float((ms * np.array(reps)[None, :]).sum() * SAMPLES / a.steps),
+        "pass": dict(device_ms=pass_time * 1e3, tflops=float(flops.sum() / pass_time / 1e12),
+                     frac_of_peak=float(flops.sum() / pass_time / 1e12 / PEAK[dtype]),
+                     what="one GEMM per row: sum of flops / sum of per-launch times"),
         "best_row_tflops": float(tflops.max()),
         "frac_of_attainable": frac_summary(tflops, rows),
         "roofline": roofline,
     }
-    # selector quality measured offline on the stored exhaustive sweep (held-out shapes)
+    # selector quality: stored (exhaustive sweep, held-out shapes) and live (this run)
     rep = os.path.join(ROOT, "paper_2003_06795_amd", "tune", "data", "tree_%s.json" % dtype)
     if os.path.exists(rep):
         R = json.load(open(rep))
@@ -293,47 +484,27 @@ def main():
                                best_single_kernel_geomean=held["best_single"],
                                held_out_by_config={c: v["selector"] for c, v in dep.get("test_by_config", {}).items()})
     if not a.no_extra and a.workload == "cfg2":
+        del bufs
+        torch.cuda.empty_cache()
+        out.setdefault("selector", {})["live"] = selector_live(ks, torch)
+        large = time_set(ks, torch, "fp32_large")
+        probe = torch.rand(ks.MFMA_PROBE_BYTES // 4, device="cuda") * 2 - 1
+        s32, mhz32 = ks.mfma_sustained(ks.F32, probe, rounds=2000)
+        for c in large:
+            c["frac_of_sustained_mfma"] = c["tflops"] / s32
+        out["fp32_large"] = dict(cells=large, best_frac_of_peak=max(c["frac_of_peak"] for c in large),
+                                 mfma_sustained=dict(tflops=s32, shader_mhz=mhz32,
+                                                     what="32x32x2 fp32 MFMAs on U[-1,1) register operands"))
+        for name in ("cfg3_sample", "cfg4"):
+            cells = time_set(ks, torch, name, iters=5)
+            out[name] = dict(rows=len(cells), geomean_tflops=geomean([c["tflops"] for c in cells]),
+                             frac_of_attainable_geomean=geomean([c["frac_of_attainable"] for c in cells]),
+                             best=max(cells, key=lambda c: c["tflops"]))
         out["bf16_large"] = bf16_report(ks, torch)
+        ks.set_workspace(None)
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(rows)
     print(json.dumps(out))
-
-
-def frac_summary(tflops, rows):
-    """Achieved / min(peak, AI x 8 TB/s) per row: geometric mean, quartiles and the maximum.  Most rows
-    of the fp32 tuning set last a few microseconds, where launch latency (not in this bound) rules."""
-    f = np.array([t / attainable_tflops(r["dtype"], r["M"], r["N"], r["K"], r["batch"])
-                  for t, r in zip(tflops, rows)])
-    q = np.quantile(f, [0.25, 0.5, 0.75])
-    return dict(geomean=float(np.exp(np.mean(np.log(f)))), q25=float(q[0]), median=float(q[1]),
-                q75=float(q[2]), max=float(f.max()))
-
-
-def bf16_report(ks, torch):
-    """Selected bf16 kernels on the large/skinny set: TFLOP/s and fraction of the bf16 matrix peak."""
-    rows = build_rows("cfg5")
-    bufs = allocate(rows, torch)
-    ws = torch.empty(64 * 256 * 256 + 4 * 8192 * 256 + 1024, dtype=torch.float32, device="cuda")
-    ks.set_workspace(ws)
-    cells = []
-    for r in rows:
-        A, B, C = bufs[(r["dtype"], r["shape"])]
-        M, N, K = r["M"], r["N"], r["K"]
-        kid = ks.select(ks.BF16, M, N, K, 1, r["tA"], r["tB"])
-        if ks.workspace_bytes_needed(ks.BF16, kid, M, N, 1) > ws.numel() * 4:
-            continue
-        t = ks.time_gemm(ks.BF16, kid, r["tA"], r["tB"], M, N, K, 1.0, A, M if r["tA"] else K, B,
-                         K if r["tB"] else N, 0.0, C, N, warmup=3, iters=10, reps=1)
-        tf = 2.0 * M * N * K / (float(np.median(t)) * 1e-3) / 1e12
-        gbs = ((M * K + K * N) * 2 + M * N * 4) / (float(np.median(t)) * 1e-3) / 1e9
-        cells.append(dict(M=M, N=N, K=K, layout="N" + "NT"[r["tB"]], kernel=kid, tflops=tf,
-                          frac_of_bf16_peak=tf / PEAK["bf16"], algorithmic_gbs=gbs,
-                          attainable_tflops=attainable_tflops("bf16", M, N, K),
-                          frac_of_attainable=tf / attainable_tflops("bf16", M, N, K)))
-    ks.set_workspace(None)
-    big = [c["tflops"] for c in cells if min(c["M"], c["N"]) >= 2048]
-    return dict(cells=cells, geomean_tflops=float(np.exp(np.mean(np.log([c["tflops"] for c in cells])))),
-                best_frac_of_peak=max(big) / PEAK["bf16"] if big else None)
 
 
 if __name__ == "__main__":

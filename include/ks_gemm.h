@@ -193,6 +193,27 @@ int ks_gemm_static_scratch(int dtype, int kernel_id, int transA, int transB, int
                            float beta, float *C, int64_t ldc,
                            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
 
+/* What a GEMM call would launch, without launching it: the same checks and decisions as
+ * ks_gemm_*_with_kernel (kernel_id >= 0) or ks_gemm_* (kernel_id < 0) with the workspace that is
+ * registered now.  For measurement tools that have to name the device function a call resolves to
+ * (a member whose split is chosen per call runs another kernel, plus the reduction pass, when it
+ * splits).  Arguments and statuses as for the GEMM calls; out: host. */
+typedef struct {
+    int32_t kernel_id;            /* the member that runs (after selection and the no-workspace fallback) */
+    int32_t split_k;              /* K partitions taken; > 1 means partial-sum kernel + reduction pass */
+    int32_t path;                 /* 0: the member's general kernel; 1: direct-to-LDS 16-bit kernel;
+                                     2: direct-to-LDS kernel in its two-groups-of-waves form */
+    int32_t vector_loads;         /* 16-byte global accesses are legal for these operands */
+    int32_t grid_3d;              /* launched (tilesN, tilesM, batch * split_k) instead of one-dimensional */
+    int32_t tiles_per_workgroup;  /* > 1: the multi-tile form of the large fp32 members */
+    int64_t workgroups;
+} ks_launch_plan_t;
+int ks_gemm_plan(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                 float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                 float beta, float *C, int64_t ldc,
+                 int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                 ks_launch_plan_t *out);
+
 /* Brute-force timing of one (workload, instantiation) cell (Section II-A: runtime recorded over a
  * number of iterations).  Runs `warmup` untimed launches, then `iters` samples; a sample is
  * `reps` back-to-back launches bracketed by one pair of HIP events on `stream`.  Synchronises and
@@ -249,6 +270,18 @@ int ks_set_tiles_per_workgroup(int n);
  * plain one-read-one-write kernel (ks::copy_kernel).  Hardware traffic counters collected over a
  * profile that contains this launch are scaled by what they report for it. */
 int ks_calibration_copy(void *dst_device, const void *src_device, size_t bytes, void *stream);
+
+/* Measurement aid: what the matrix pipe alone sustains on given operand VALUES (the clock this
+ * device holds under matrix load depends on the bit patterns the instructions chew on).  2048
+ * work-groups of eight waves load twelve 16-byte fragments per lane once from `operands_device`
+ * (at least KS_MFMA_PROBE_BYTES, 16-byte aligned; pass the A operand of the GEMM in question) and
+ * issue `rounds` x 32 dependent-free 32x32 MFMAs of `dtype` each, with no LDS or memory traffic.
+ * Runs the kernel twice on `stream`, synchronises, and reports the second run: TFLOP/s from HIP
+ * events and, if mhz_out != NULL, the shader clock of work-group 0 (cycle counter over the
+ * 100 MHz reference counter).  1 <= rounds <= 2^24.  Not thread-safe against itself. */
+#define KS_MFMA_PROBE_BYTES (64u * 8u * 12u * 1024u)
+int ks_mfma_sustained(int dtype, const void *operands_device, size_t bytes, int rounds, void *stream,
+                      double *tflops_out, double *mhz_out);
 
 /* ---------------------------------------------------------------- workspace
  * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no

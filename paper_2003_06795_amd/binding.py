@@ -31,6 +31,12 @@ class KernelInfo(ctypes.Structure):
         return d
 
 
+class LaunchPlan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("kernel_id", "split_k", "path", "vector_loads", "grid_3d", "tiles_per_workgroup")] + \
+               [("workgroups", ctypes.c_int64)]
+
+
 class TreeNode(ctypes.Structure):
     _fields_ = [("feature", ctypes.c_int32), ("left", ctypes.c_int32), ("right", ctypes.c_int32),
                 ("value", ctypes.c_int32), ("threshold", ctypes.c_int64)]
@@ -53,7 +59,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
-    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_time_gemm", "ks_calibration_copy", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
+    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
@@ -84,6 +90,7 @@ def lib():
     L.ks_gemm_bias.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
     L.ks_gemm_out_bf16.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
     L.ks_gemm_static_scratch.argtypes = [_i, _i] + _GEMM
+    L.ks_gemm_plan.argtypes = [_i, _i] + _GEMM[:-1] + [ctypes.POINTER(LaunchPlan)]
     L.ks_time_gemm.argtypes = [_i, _i] + _GEMM + [_i, _i, _i, _p]
     L.ks_num_kernels.argtypes = [_i]
     L.ks_kernel_info.argtypes = [_i, _i, ctypes.POINTER(KernelInfo)]
@@ -92,6 +99,7 @@ def lib():
     L.ks_set_selector.argtypes = [_i, _p, _i]
     L.ks_get_selector.argtypes = [_i, _p, _i]
     L.ks_calibration_copy.argtypes = [_p, _p, ctypes.c_size_t, _p]
+    L.ks_mfma_sustained.argtypes = [_i, _p, ctypes.c_size_t, _i, _p, _p, _p]
     L.ks_set_fast_path.argtypes = [_i]
     L.ks_set_tiles_per_workgroup.argtypes = [_i]
     L.ks_set_workspace.argtypes = [_p, ctypes.c_size_t]
@@ -215,6 +223,16 @@ def gemm_static_scratch(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda
                                                 batch, strideA, strideB, strideC, stream)), "ks_gemm_static_scratch")
 
 
+def gemm_plan(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+              batch=1, strideA=0, strideB=0, strideC=0):
+    """What the call would launch (dict of ks_launch_plan_t), without launching."""
+    out = LaunchPlan()
+    a = _gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batch, strideA, strideB,
+                   strideC, 0)
+    _check(lib().ks_gemm_plan(int(dtype), int(kernel_id), *a[:-1], ctypes.byref(out)), "ks_gemm_plan")
+    return {n: int(getattr(out, n)) for n, _ in LaunchPlan._fields_}
+
+
 def time_gemm(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
               batch=1, strideA=0, strideB=0, strideC=0, stream=None, warmup=3, iters=10, reps=1):
     """Per-launch milliseconds of `iters` samples (numpy float32)."""
@@ -274,6 +292,19 @@ def get_selector(dtype):
 
 def calibration_copy(dst, src, nbytes, stream=None):
     _check(lib().ks_calibration_copy(_dev(dst), _dev(src), int(nbytes), _stream(stream)), "ks_calibration_copy")
+
+
+MFMA_PROBE_BYTES = 64 * 8 * 12 * 1024
+
+
+def mfma_sustained(dtype, operands, nbytes=None, rounds=2000, stream=None):
+    """(TFLOP/s, shader MHz) of a pure MFMA loop on the values in `operands` (device buffer)."""
+    if nbytes is None:
+        nbytes = operands.numel() * operands.element_size()
+    tf, mhz = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().ks_mfma_sustained(int(dtype), _dev(operands), int(nbytes), int(rounds), _stream(stream),
+                                   ctypes.byref(tf), ctypes.byref(mhz)), "ks_mfma_sustained")
+    return tf.value, mhz.value
 
 
 def set_fast_path(enabled):

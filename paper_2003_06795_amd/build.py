@@ -38,8 +38,9 @@ def _jobs():
             src = os.path.join(CSRC, "instances_%s.hip" % kind)
             jobs.append((src, os.path.join(OBJ, "inst_%s_%02d.o" % (kind, n)),
                          [HIPCC] + HIP_FLAGS + ["-DKS_SHARD=%d" % n, "-c", src]))
-    src = os.path.join(CSRC, "dispatch.hip")
-    jobs.append((src, os.path.join(OBJ, "dispatch.o"), [HIPCC] + HIP_FLAGS + ["-c", src]))
+    for name in ("dispatch", "measure"):
+        src = os.path.join(CSRC, name + ".hip")
+        jobs.append((src, os.path.join(OBJ, name + ".o"), [HIPCC] + HIP_FLAGS + ["-c", src]))
     for name in ("selector", "tune"):
         src = os.path.join(CSRC, name + ".cpp")
         jobs.append((src, os.path.join(OBJ, name + ".o"), ["g++"] + CXX_FLAGS + ["-c", src]))

@@ -251,12 +251,19 @@ Workspace registered_ws() { return Workspace{g_ws, g_wsBytes}; }
 int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
            const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
-           const float *bias = nullptr, int out16 = 0) {
+           const float *bias = nullptr, int out16 = 0, ks_launch_plan_t *planOnly = nullptr) {
     const InstanceDesc *d = desc_of(dtype, id);
     if (!d) return KS_ERR_INVALID_ARG;
     const int rc = validate(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, batch, strideC);
     if (rc != KS_OK) return rc;
+    if (planOnly) {
+        *planOnly = ks_launch_plan_t{};
+        planOnly->kernel_id = id;
+        planOnly->split_k = 1;
+        planOnly->tiles_per_workgroup = 1;
+    }
     if (M == 0 || N == 0 || batch == 0) return KS_OK;
+    if (planOnly && K == 0) return KS_OK;
     std::call_once(g_once, init_tables);
 
     // An error left behind by an earlier, unrelated runtime call must not be blamed on this launch.
@@ -329,6 +336,19 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
     const int f16Bit = dtype == KS_F16 ? 16 : 0;     // same 16-bit members, binary16 MFMA
     const bool dma = dtype != KS_F32 && vec && g_forceGeneric == 0 && K % d->bk == 0 &&
                      lda <= (1LL << 22) && ldb <= (1LL << 22);
+    if (planOnly) {
+        planOnly->split_k = p.splitK;
+        planOnly->vector_loads = vec ? 1 : 0;
+        planOnly->grid_3d = p.grid3d;
+        planOnly->tiles_per_workgroup = p.tilesPerWG;
+        planOnly->workgroups = grid64;
+        planOnly->path = !dma ? 0
+                         : bf16_two_groups(d->core == KS_CORE_MFMA32 ? 32 : 16, d->bm, d->bn, d->bk, d->p1, d->p2,
+                                           d->ldsBytes / (d->bk * (d->bm + d->bn) * 2))
+                             ? 2
+                             : 1;
+        return KS_OK;
+    }
     if (dma)
         g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0) + splitBit + f16Bit, stream);
     else
@@ -589,6 +609,20 @@ extern "C" int ks_gemm_static_scratch(int dtype, int kernel_id, int transA, int 
         if (kernel_id < 0) return kernel_id;
     }
     return run_ws(w, dtype, kernel_id, KS_GEMM_PASS);
+}
+
+extern "C" int ks_gemm_plan(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                            float alpha, const void *A, int64_t lda, const void *B, int64_t ldb, float beta,
+                            float *C, int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,
+                            int64_t strideC, ks_launch_plan_t *out) {
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
+    if (!out) return KS_ERR_INVALID_ARG;
+    if (kernel_id < 0) {
+        kernel_id = select_checked(dtype, M, N, K, batch, transA, transB);
+        if (kernel_id < 0) return kernel_id;
+    }
+    void *stream = nullptr;
+    return run_ws(registered_ws(), dtype, kernel_id, KS_GEMM_PASS, nullptr, 0, out);
 }
 
 extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,

@@ -2,35 +2,33 @@
 // K-step of the templated kernel) in its "two groups of waves" form for gfx950.
 //
 // The eight waves of a work-group form two groups of four; a SIMD holds one wave of each group.
-// Every K-step is cut into four pairs of slots, a memory slot (LDS -> register fragment reads and
-// the issue of direct-to-LDS global loads) followed by a compute slot (eight 32x32x16 or sixteen
-// 16x16x32 MFMAs), each slot closed by s_barrier.  The second group runs one slot behind the
-// first, so on every SIMD one wave streams MFMAs while the other feeds the memory pipes.
+// Every K-step is cut into two pairs of slots, a memory slot (LDS -> register fragment reads and
+// the issue of direct-to-LDS global loads) followed by a compute slot (sixteen 32x32x16 or
+// thirty-two 16x16x32 MFMAs, 512 clocks of the matrix pipe), each slot closed by s_barrier.  The
+// second group runs one slot behind the first, so on every SIMD one wave streams MFMAs while the
+// other feeds the memory pipes, and the matrix pipe never waits for an LDS read or a load issue.
 //
 // Tile decomposition: the 256 x 256 tile is four 128 x 128 quadrants (i, j); wave (wr, wc) of the
-// 2 x 4 wave grid owns the 64 x 32 block at rows wr*64, columns wc*32 of each quadrant.  The
-// operand tiles live in LDS as halves A0, A1 (rows 0..127 / 128..255 of the A tile) and B0, B1,
-// two stages each; a half is released as soon as the slot that consumes it has passed, and is
-// refilled at once with the K-step after next, so loads run about 1.5 K-steps ahead of their
-// use with two stages (128 KB) of LDS.
+// 2 x 4 wave grid owns the 64 x 32 block at rows wr*64, columns wc*32 of each quadrant (128 x 64
+// entries per wave in all).  The operand tiles live in LDS as halves A0, A1 (rows 0..127 /
+// 128..255 of the A tile) and B0, B1, two stages each (128 KB); a half is released by the barrier
+// behind the second group's slot that reads it and is refilled at once with the K-step after
+// next, so loads run 1.5 K-steps ahead of their use although there are only two stages.
 //
 // Slots of K-step t (stage s = t & 1), per wave:
-//   M0  read A0, B0 fragments      issue A1(t+1) -> stage s^1        wait: B1(t) landed
-//   C0  quadrant (0,0)
-//   M1  read B1 fragments                                            wait: A1(t) landed
-//   C1  quadrant (0,1)
-//   M2  read A1 fragments          issue A0(t+2), B0(t+2) -> stage s
-//   C2  quadrant (1,1)
-//   M3                             issue B1(t+2) -> stage s          wait: A0(t+1), B0(t+1) landed
-//   C3  quadrant (1,0)
-// A wave waits (s_waitcnt vmcnt) for its own part of a half before the barrier that precedes the
-// slot in which any wave reads that half.  Preconditions are those of gemm_bf16_dma.hpp.
+//   M0  read A0, B0, B1 fragments   issue A1(t+1) -> stage s^1             wait: A1(t) landed
+//   C0  quadrants (0,0), (0,1)
+//   M1  read A1 fragments           issue A0, B0, B1 (t+2) -> stage s      wait: A0, B0, B1 (t+1) landed
+//   C1  quadrants (1,1), (1,0)
+// A memory slot ends with the wave's own LDS reads complete (so the half may be overwritten after
+// the barrier) and with the wave's own part of the half read next complete (s_waitcnt vmcnt); the
+// barrier then publishes both to the work-group.  Loads are issued in the fixed order
+// [A0 B0 B1](u), A1(u), [A0 B0 B1](u+1), ... so each wait leaves exactly the eight youngest loads
+// in flight.  Past the end of the K range the same loads are issued on the last K-step's
+// addresses into halves nobody reads any more: every step is the same straight-line code.
+// Preconditions are those of gemm_bf16_dma.hpp.
 #pragma once
 #include "gemm_bf16_dma.hpp"
-
-#ifndef KS_PP_SLOTS
-#define KS_PP_SLOTS 8
-#endif
 
 namespace ks {
 
@@ -80,8 +78,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     constexpr int FM = 64 / F, FN = 32 / F;                  // fragments of a wave's 64 x 32 block
     constexpr int KSTEP = F == 32 ? 16 : 32, NSUB = BK / KSTEP;
     constexpr int HB = HALF * BK * 2;                        // bytes of one half tile
-    // one LDS object per (operand, stage, half): in-flight loads into one never alias the reads of another
-    __shared__ __attribute__((aligned(1024))) char A00[HB];
+    __shared__ __attribute__((aligned(1024))) char A00[HB];  // A<stage><half>
     __shared__ __attribute__((aligned(1024))) char A01[HB];
     __shared__ __attribute__((aligned(1024))) char A10[HB];
     __shared__ __attribute__((aligned(1024))) char A11[HB];
@@ -92,9 +89,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-#ifdef KS_PP_TRACE
-    const unsigned long long clk0 = __builtin_amdgcn_s_memtime(), rt0 = __builtin_amdgcn_s_memrealtime();
-#endif
     const int wr = wave >> 2, wc = wave & 3;
     const TileCoord tc = tile_of_block(p);
     const int row0 = tc.tm * BM, col0 = tc.tn * BN;
@@ -135,6 +129,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
 
     bf16x8 a[FM][NSUB], b0[FN][NSUB], b1[FN][NSUB];
 
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
     auto lds_a = [&](auto s, auto h) -> char * {
         constexpr int S = decltype(s)::value, H = decltype(h)::value;
         return S == 0 ? (H == 0 ? A00 : A01) : (H == 0 ? A10 : A11);
@@ -143,9 +139,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         constexpr int S = decltype(s)::value, H = decltype(h)::value;
         return S == 0 ? (H == 0 ? B00 : B01) : (H == 0 ? B10 : B11);
     };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-
     auto read_a = [&](const char *half) {
 #pragma unroll
         for (int m = 0; m < FM; ++m)
@@ -162,7 +155,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     };
     auto mma = [&](auto qi, auto qj, const bf16x8 (&b)[FN][NSUB]) {
         constexpr int QI = decltype(qi)::value, QJ = decltype(qj)::value;
-        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int ks = 0; ks < NSUB; ++ks)
 #pragma unroll
@@ -174,7 +166,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
                     else
                         acc32[QI][QJ][m][n] = mfma_32x32x16<F16>(a[m][ks], b[n][ks], acc32[QI][QJ][m][n]);
                 }
-        __builtin_amdgcn_s_setprio(0);
     };
     // end of a slot: nothing moves across it, then the work-group barrier
     auto slot_end = [&]() {
@@ -182,67 +173,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
-#ifdef KS_PP_TRACE
-    unsigned long long stamp[16];
-#define KS_PP_STAMP(i) stamp[i] = __builtin_amdgcn_s_memtime()
-#else
-#define KS_PP_STAMP(i)
-#endif
-
-#ifndef KS_PP_ABLATE
-#define KS_PP_ABLATE 0
-#endif
-#if KS_PP_ABLATE & 1
-#define KS_PP_IF_LOADS(x)
-#else
-#define KS_PP_IF_LOADS(x) x
-#endif
-#if KS_PP_ABLATE & 2
-#define KS_PP_IF_READS(x) if (t < 2) { x; }
-#else
-#define KS_PP_IF_READS(x) x
-#endif
-#if KS_PP_SLOTS == 4
-    // One K-step in two slot pairs.  Issue order of the loads: [A0 B0 B1](u) in M1(u-2), A1(u) in
-    // M0(u-1).  Every memory slot ends with its own LDS reads complete, so a half is free as soon as
-    // the barrier behind the second group's reading slot has been passed.
-    auto wait_lds = [&]() { __builtin_amdgcn_s_waitcnt(0xC07F); };      // lgkmcnt(0) only
-    auto step = [&](int t, auto s) {
-        constexpr int S = decltype(s)::value;
-        using SC = std::integral_constant<int, S>;
-        using SN = std::integral_constant<int, S ^ 1>;
-        const int t1 = min(t + 1, nk - 1), t2 = min(t + 2, nk - 1);
-        // M0
-        KS_PP_IF_READS(read_a(lds_a(SC{}, I0{})));
-        KS_PP_IF_READS(read_b(lds_b(SC{}, I0{}), b0));
-        KS_PP_IF_READS(read_b(lds_b(SC{}, I1{}), b1));
-        KS_PP_IF_LOADS(pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave));
-        wait_vmcnt<8>();                                     // A1(t) landed
-        wait_lds();
+    // end of a memory slot: at most the eight youngest loads of this wave still in flight and all
+    // of its LDS reads returned (vmcnt(8), lgkmcnt(0); the export counter is left alone)
+    auto memory_slot_end = [&]() {
+        wait_vmcnt<8>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);
         slot_end();
-        KS_PP_STAMP(S * 8 + 0);
-        mma(I0{}, I0{}, b0);
-        mma(I0{}, I1{}, b1);
-        slot_end();
-        KS_PP_STAMP(S * 8 + 1);
-        // M1
-        KS_PP_IF_READS(read_a(lds_a(SC{}, I1{})));
-        KS_PP_IF_LOADS(pa0.issue(aTile + t2 * aStep, lds_a(SC{}, I0{}), wave));
-        KS_PP_IF_LOADS(pb0.issue(bTile + t2 * bStep, lds_b(SC{}, I0{}), wave));
-        KS_PP_IF_LOADS(pb1.issue(bTile + t2 * bStep, lds_b(SC{}, I1{}), wave));
-        wait_vmcnt<8>();                                     // A0, B0, B1 (t+1) landed
-        wait_lds();
-        slot_end();
-        KS_PP_STAMP(S * 8 + 2);
-        mma(I1{}, I1{}, b1);
-        mma(I1{}, I0{}, b0);
-        slot_end();
-        KS_PP_STAMP(S * 8 + 3);
     };
-#else
-    // One K-step.  Past the end of the K range the loads are issued all the same, on the last
-    // K-step's addresses and into halves nobody reads any more, so that every step is the same
-    // straight-line code and the waits can count on a fixed number of younger loads.
+
     auto step = [&](int t, auto s) {
         constexpr int S = decltype(s)::value;
         using SC = std::integral_constant<int, S>;
@@ -251,41 +189,28 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         // M0
         read_a(lds_a(SC{}, I0{}));
         read_b(lds_b(SC{}, I0{}), b0);
-        pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave);
-        wait_vmcnt<10>();
-        slot_end();
-        KS_PP_STAMP(S * 8 + 0);
-        mma(I0{}, I0{}, b0);
-        slot_end();
-        KS_PP_STAMP(S * 8 + 1);
-        // M1
         read_b(lds_b(SC{}, I1{}), b1);
-        wait_vmcnt<8>();
-        slot_end();
-        KS_PP_STAMP(S * 8 + 2);
+        pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave);
+        memory_slot_end();
+        // C0: the wave that is issuing MFMAs goes ahead of the one issuing memory instructions
+        __builtin_amdgcn_s_setprio(1);
+        mma(I0{}, I0{}, b0);
         mma(I0{}, I1{}, b1);
+        __builtin_amdgcn_s_setprio(0);
         slot_end();
-        KS_PP_STAMP(S * 8 + 3);
-        // M2
+        // M1
         read_a(lds_a(SC{}, I1{}));
         pa0.issue(aTile + t2 * aStep, lds_a(SC{}, I0{}), wave);
         pb0.issue(bTile + t2 * bStep, lds_b(SC{}, I0{}), wave);
-        slot_end();
-        KS_PP_STAMP(S * 8 + 4);
-        mma(I1{}, I1{}, b1);
-        slot_end();
-        KS_PP_STAMP(S * 8 + 5);
-        // M3
         pb1.issue(bTile + t2 * bStep, lds_b(SC{}, I1{}), wave);
-        wait_vmcnt<10>();
-        slot_end();
-        KS_PP_STAMP(S * 8 + 6);
+        memory_slot_end();
+        // C1
+        __builtin_amdgcn_s_setprio(1);
+        mma(I1{}, I1{}, b1);
         mma(I1{}, I0{}, b0);
+        __builtin_amdgcn_s_setprio(0);
         slot_end();
-        KS_PP_STAMP(S * 8 + 7);
     };
-
-#endif
 
     // A work-group whose K partition is empty (possible for the last split-K partition) only
     // writes zeros; the branch is uniform over the work-group, so the barriers stay matched.
@@ -299,40 +224,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         pa0.issue(aTile + s1 * aStep, lds_a(I1{}, I0{}), wave);
         pb0.issue(bTile + s1 * bStep, lds_b(I1{}, I0{}), wave);
         pb1.issue(bTile + s1 * bStep, lds_b(I1{}, I1{}), wave);
-#if KS_PP_SLOTS == 4
         wait_vmcnt<8>();
-#else
-        wait_vmcnt<10>();
-#endif
         slot_end();
         if (wr == 1) slot_end();                             // the second group starts one slot later
 
         int t = 0;
-#ifdef KS_PP_TRACE
-        const int nkLoop = nk - 6;      // stop early: the traced steps still prefetch real K-steps
-        for (; t + 2 <= nkLoop; t += 2) {
-#else
         for (; t + 2 <= nk; t += 2) {
-#endif
             step(t, I0{});
             step(t + 1, I1{});
         }
-#ifndef KS_PP_TRACE
         if (t < nk) step(t, I0{});
-#endif
         // the loads issued past the end must have landed before this work-group's LDS is given away
         wait_vmcnt<0>();
-#ifdef KS_PP_TRACE
-        if (blockIdx.x < 64 && lane == 0) {
-            unsigned long long *tr = reinterpret_cast<unsigned long long *>(p.ws) + (blockIdx.x * 8 + wave) * 16;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) tr[i] = stamp[i];
-            if (wave == 0) {
-                unsigned long long *c = reinterpret_cast<unsigned long long *>(p.ws) + 64 * 8 * 16 + blockIdx.x * 4;
-                c[0] = clk0; c[1] = rt0; c[2] = __builtin_amdgcn_s_memtime(); c[3] = __builtin_amdgcn_s_memrealtime();
-            }
-        }
-#endif
         if (wr == 0) slot_end();                             // pairs with the second group's last slot
     }
 

@@ -13,7 +13,7 @@ namespace ks {
 // The eight-wave 256 x 256 x 64 members (128 x 64 of output per wave) run in the form with two
 // groups of waves alternating between memory and MFMA slots (gemm_bf16_pp.hpp).
 template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES>
-constexpr bool kTwoGroups = F == 32 && BM == 256 && BN == 256 && BK == 64 && WM == 128 && WN == 64 && STAGES == 2;
+constexpr bool kTwoGroups = bf16_two_groups(F, BM, BN, BK, WM, WN, STAGES);
 
 // variant = akc * 2 + bkc
 template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES, bool SPLIT>

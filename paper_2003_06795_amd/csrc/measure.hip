@@ -1,0 +1,107 @@
+// Measurement aids behind the C ABI: what the matrix pipe alone sustains on given operand values.
+// Nothing here is on the GEMM path.
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+
+#include "../../include/ks_gemm.h"
+#include "gemm_bf16.hpp"
+
+namespace ks {
+namespace {
+
+__device__ unsigned long long g_probeClocks[2];      // shader clocks, 100 MHz reference ticks (work-group 0)
+
+// Every wave loads twelve 16-byte operand fragments per lane once (what one K-step of a 128 x 64
+// wave tile holds), then issues `rounds` x 32 MFMAs on them into eight accumulator fragments:
+// no LDS, no memory traffic, two waves per SIMD.  KIND 0: 32x32x16 bf16, 1: 32x32x16 f16,
+// 2: 32x32x2 f32.
+template <int KIND>
+__global__ __launch_bounds__(512) void mfma_sustained_kernel(const uintx4 *src, int rounds, float *sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uintx4 *mine = src + ((size_t)((blockIdx.x & 63) * 8 + wave) * 12) * 64 + lane;
+    uintx4 a[8], b[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = mine[i * 64];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = mine[(8 + i) * 64];
+    floatx16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    unsigned long long c0 = 0, r0 = 0;
+    const bool stamp = blockIdx.x == 0 && threadIdx.x == 0;
+    if (stamp) { c0 = __builtin_amdgcn_s_memtime(); r0 = __builtin_amdgcn_s_memrealtime(); }
+    for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    floatx16 &c = acc[q * 2 + m];
+                    if constexpr (KIND == 2)
+                        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a[m * 4 + ks][q]),
+                                                                 __builtin_bit_cast(float, b[ks][q]), c, 0, 0, 0);
+                    else
+                        c = mfma_32x32x16<KIND == 1>(__builtin_bit_cast(bf16x8, a[m * 4 + ks]),
+                                                     __builtin_bit_cast(bf16x8, b[ks]), c);
+                }
+    }
+    if (stamp) {
+        g_probeClocks[0] = __builtin_amdgcn_s_memtime() - c0;
+        g_probeClocks[1] = __builtin_amdgcn_s_memrealtime() - r0;
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    if (sink != nullptr && s == 123.4567f) sink[threadIdx.x] = s;     // keeps the accumulators alive
+}
+
+std::mutex g_probeMutex;
+
+}  // namespace
+}  // namespace ks
+
+using namespace ks;
+
+extern "C" int ks_mfma_sustained(int dtype, const void *operands_device, size_t bytes, int rounds,
+                                 void *stream, double *tflops_out, double *mhz_out) {
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
+    if (!operands_device || bytes < KS_MFMA_PROBE_BYTES || rounds < 1 || rounds > (1 << 24) || !tflops_out)
+        return KS_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(operands_device) % 16) return KS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_probeMutex);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    (void)hipGetLastError();
+    if (hipEventCreate(&e0) != hipSuccess) return KS_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return KS_ERR_LAUNCH; }
+    const int groups = 256 * 8;
+    const uintx4 *src = static_cast<const uintx4 *>(operands_device);
+    int rc = KS_OK;
+    float ms = 0.f;
+    for (int pass = 0; pass < 2 && rc == KS_OK; ++pass) {            // the first pass settles the clock
+        if (hipEventRecord(e0, s) != hipSuccess) rc = KS_ERR_LAUNCH;
+        if (dtype == KS_BF16) hipLaunchKernelGGL(mfma_sustained_kernel<0>, dim3(groups), dim3(512), 0, s, src, rounds, (float *)nullptr);
+        else if (dtype == KS_F16) hipLaunchKernelGGL(mfma_sustained_kernel<1>, dim3(groups), dim3(512), 0, s, src, rounds, (float *)nullptr);
+        else hipLaunchKernelGGL(mfma_sustained_kernel<2>, dim3(groups), dim3(512), 0, s, src, rounds, (float *)nullptr);
+        if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess ||
+            hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+            rc = KS_ERR_LAUNCH;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != KS_OK) return rc;
+    const double flopPerMfma = dtype == KS_F32 ? 2.0 * 32 * 32 * 2 : 2.0 * 32 * 32 * 16;
+    *tflops_out = (double)groups * 8 * (double)rounds * 32 * flopPerMfma / ((double)ms * 1e-3) / 1e12;
+    if (mhz_out) {
+        unsigned long long h[2] = {0, 0};
+        if (hipMemcpyFromSymbol(h, HIP_SYMBOL(g_probeClocks), sizeof(h)) != hipSuccess) return KS_ERR_LAUNCH;
+        *mhz_out = h[1] ? (double)h[0] / ((double)h[1] * 0.01) : 0.0;
+    }
+    return KS_OK;
+}
