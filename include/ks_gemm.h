@@ -50,7 +50,8 @@ typedef enum {
     KS_OK = 0,
     KS_ERR_INVALID_ARG = -1,   /* bad flag, negative size, short leading dimension, NULL operand,
                                   overlapping batch items of C, id out of range */
-    KS_ERR_UNSUPPORTED = -2,   /* size beyond the 32-bit tile arithmetic of the kernels */
+    KS_ERR_UNSUPPORTED = -2,   /* size beyond the 32-bit tile arithmetic of the kernels; a member that a
+                                  pruned build does not contain */
     KS_ERR_LAUNCH = -3,        /* the HIP runtime refused the launch / no device */
     KS_ERR_WORKSPACE = -4      /* a split-K kernel needs a larger registered workspace */
 } ks_status;
@@ -82,6 +83,9 @@ typedef struct {
                             slice and wave tile for core KS_CORE_KSLICE, one complete group of waves
                             (threads / k_waves lanes, its own LDS stages) per slice for the LDS-staged
                             MFMA cores; 1 = none */
+    int32_t available;   /* 1: compiled into this library; 0: pruned away (a library built with only the
+                            kept set of the deployed trees, Section III, holds the kept members and the
+                            four bring-up tiles; forcing an absent member returns KS_ERR_UNSUPPORTED) */
 } ks_kernel_info_t;
 
 /* Node of a deployed decision tree (Section IV: nested integer comparisons).

@@ -238,6 +238,35 @@ def prune_and_train(X_train, P_train, n_kept, max_depth=12, min_samples_leaf=1):
     return dict(regression_tree=reg, kept=kept, labels=y, selector=clf)
 
 
+def prune_and_train_by_regime(X_train, P_train, n_single, n_batched, batch_feature=3, max_depth=12,
+                              min_samples_leaf=1):
+    """The pipeline applied per regime (reading: the paper has one kind of workload; here single
+    GEMMs, batch count 1, and batched ones differ in what wins and in how many rows describe them,
+    and a pooled pruning tree of Section III spends its leaves where the rows are).  Rows with
+    feature[batch_feature] <= 1 are pruned to at most n_single leaves and classified on their own,
+    the others with n_batched; the deployed selector is a root "batch <= 1" whose children are the
+    two classifiers, i.e. still one tree of nested integer comparisons (Section IV).
+    Returns dict(kept, selector, parts) where selector is a node list in the layout of
+    fit_classification_tree (node 0 the root, left subtree first)."""
+    X_train, P_train = np.asarray(X_train, dtype=np.int64), np.asarray(P_train, dtype=np.float64)
+    single = X_train[:, batch_feature] <= 1
+    if single.all() or not single.any():
+        whole = prune_and_train(X_train, P_train, n_single, max_depth, min_samples_leaf)
+        return dict(kept=whole["kept"], selector=whole["selector"], parts=[whole])
+    one = prune_and_train(X_train[single], P_train[single], n_single, max_depth, min_samples_leaf)
+    many = prune_and_train(X_train[~single], P_train[~single], n_batched, max_depth, min_samples_leaf)
+    root = _leaf(np.arange(X_train.shape[0]), label=one["selector"][0]["label"])
+    root.update(feature=batch_feature, threshold=1, left=1, right=1 + len(one["selector"]))
+    joined = [root]
+    for offset, part in ((1, one["selector"]), (1 + len(one["selector"]), many["selector"])):
+        for nd in part:
+            c = dict(nd)
+            if c["feature"] != -1:
+                c["left"], c["right"] = c["left"] + offset, c["right"] + offset
+            joined.append(c)
+    return dict(kept=sorted(set(one["kept"]) | set(many["kept"])), selector=joined, parts=[one, many])
+
+
 def sampled_prune_and_train(X_train, P_train, stage1_rows, n_kept, max_depth=12, min_samples_leaf=1):
     """A two-stage form of the same pipeline for a configuration space too large to time in full
     (the paper's conclusion names this as the open problem; the reading is ours): only the rows

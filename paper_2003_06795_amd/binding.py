@@ -11,7 +11,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libks_gemm.so")
+# KS_GEMM_LIBRARY=libks_gemm_kept.so loads the pruned build (kept members only) instead
+LIB_PATH = os.path.join(_HERE, os.environ.get("KS_GEMM_LIBRARY", "libks_gemm.so"))
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_WORKSPACE = 0, -1, -2, -3, -4
 F32, BF16, F16 = 0, 1, 2
@@ -23,7 +24,7 @@ FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "mi
 class KernelInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("id", "dtype", "core", "bm", "bn", "bk", "wm", "wn", "tm", "tn", "threads",
-                 "split_k", "lds_bytes", "k_waves")]
+                 "split_k", "lds_bytes", "k_waves", "available")]
 
     def as_dict(self):
         d = {n: int(getattr(self, n)) for n, _ in self._fields_}

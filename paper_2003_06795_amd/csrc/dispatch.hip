@@ -92,25 +92,39 @@ void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
 // K partitions for an instance whose split is chosen per call.  Work-groups run in rounds of
-// `slots` (256 compute units times the work-groups that fit one, taken as twelve waves per unit);
-// a work-group costs its K-steps plus a fixed prologue/epilogue, and splitting adds the reduction
-// pass.  The cheapest count wins (the smaller one on ties); never more than 64, never more than
-// fills one round, and at least two K-steps per partition.
-int64_t auto_split_max(const InstanceDesc *d, int64_t tiles) {
+// `slots` (256 compute units times the work-groups that fit one); a work-group costs its K-steps
+// plus a fixed prologue/epilogue, and splitting adds the reduction pass.  The cheapest count wins
+// (the smaller one on ties); never more than 64 (fp32) or 256 (16-bit), never more than fills one
+// round, and at least two K-steps per partition.
+//   fp32 members: twelve waves per compute unit, cost in K-steps as measured on the tuning set.
+//   16-bit members: their LDS stages (up to 144 KB) limit a compute unit to one to four
+//   work-groups, and a partition's tile of partial sums (written, then read by the reduction
+//   pass) is charged in units of one K-step's operand traffic, 4 BM BN / ((BM + BN) BK).
+int64_t split_slots(const InstanceDesc *d, bool f32) {
     const int64_t waves = d->threads / 64;
-    const int64_t slots = 256 * (12 / waves > 0 ? 12 / waves : 1);
-    const int64_t s = (slots + tiles - 1) / (tiles > 0 ? tiles : 1);
-    return s < 1 ? 1 : (s > 64 ? 64 : s);
+    int64_t perCU = 12 / waves > 0 ? 12 / waves : 1;
+    if (!f32) {
+        const int64_t byLds = d->ldsBytes > 0 ? (160 * 1024) / d->ldsBytes : perCU;
+        perCU = byLds < perCU ? (byLds > 0 ? byLds : 1) : perCU;
+    }
+    return 256 * perCU;
 }
 
-int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles) {
-    const int64_t waves = d->threads / 64;
-    const int64_t slots = 256 * (12 / waves > 0 ? 12 / waves : 1);
+int64_t auto_split_max(const InstanceDesc *d, int64_t tiles, bool f32) {
+    const int64_t slots = split_slots(d, f32);
+    const int64_t s = (slots + tiles - 1) / (tiles > 0 ? tiles : 1);
+    const int64_t cap = f32 ? 64 : 256;
+    return s < 1 ? 1 : (s > cap ? cap : s);
+}
+
+int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles, bool f32) {
+    const int64_t slots = split_slots(d, f32);
+    const int64_t partial = f32 ? 0 : (4LL * d->bm * d->bn) / ((int64_t)(d->bm + d->bn) * d->bk);
     int64_t best = 1, bestCost = -1;
-    const int64_t smax = auto_split_max(d, tiles);
+    const int64_t smax = auto_split_max(d, tiles, f32);
     for (int64_t s = 1; s <= smax && (s == 1 || 2 * s <= kTiles); ++s) {
         const int64_t rounds = (tiles * s + slots - 1) / slots;
-        const int64_t cost = rounds * ((kTiles + s - 1) / s + 6) + (s > 1 ? 10 : 0);
+        const int64_t cost = rounds * ((kTiles + s - 1) / s + 6 + (s > 1 ? partial : 0)) + (s > 1 ? 10 : 0);
         if (bestCost < 0 || cost < bestCost) { bestCost = cost; best = s; }
     }
     return best;
@@ -277,6 +291,9 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
         return hipGetLastError() == hipSuccess ? KS_OK : KS_ERR_LAUNCH;
     }
 
+    // a pruned build holds only the kept members
+    if ((dtype == KS_F32 ? g_f32[id] : g_bf16[id]) == nullptr) return KS_ERR_UNSUPPORTED;
+
     GemmParams p;
     p.A = A; p.B = B; p.C = C; p.ws = nullptr; p.bias = bias; p.out16 = out16;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
@@ -291,7 +308,7 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
         // automatic split: as many K partitions as fill the device, at least two K-steps each,
         // and no more than the registered workspace can hold (1 = the plain single-kernel form)
         const int64_t steps = (kTiles + d->kw - 1) / d->kw;
-        int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch, steps);
+        int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch, steps, dtype == KS_F32);
         const size_t per = (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
         if (!wsp.ptr) s = 1;
         else if ((size_t)s * per > wsp.bytes) s = (int64_t)(wsp.bytes / per);
@@ -411,6 +428,8 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     out->threads = d->threads;
     out->split_k = d->splitK;
     out->lds_bytes = d->ldsBytes;
+    std::call_once(g_once, init_tables);
+    out->available = (dtype == KS_F32 ? g_f32[kernel_id] : g_bf16[kernel_id]) != nullptr ? 1 : 0;
     return KS_OK;
 }
 
@@ -455,7 +474,7 @@ extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M,
     if (!d || d->splitK == 1 || M <= 0 || N <= 0 || batch <= 0) return 0;
     int64_t s = d->splitK;
     if (s == 0) {
-        s = auto_split_max(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch);
+        s = auto_split_max(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch, dtype == KS_F32);
         if (s <= 1) return 0;
     }
     return (size_t)s * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
@@ -477,10 +496,12 @@ static int select_checked(int dtype, int64_t M, int64_t N, int64_t K, int64_t ba
     const size_t need = (size_t)d->splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
     if (w.ptr && w.bytes >= need) return id;
     const int n = dtype == KS_F32 ? kNumF32 : kNumBf16;
+    std::call_once(g_once, init_tables);
     for (int pass = 0; pass < 2; ++pass)          // same K-step first, then any K-step
         for (int i = 0; i < n; ++i) {
             const InstanceDesc *e = desc_of(dtype, i);
-            if (e->splitK == 1 && e->core == d->core && e->bm == d->bm && e->bn == d->bn &&
+            if ((dtype == KS_F32 ? g_f32[i] : g_bf16[i]) != nullptr &&      // present in a pruned build
+                e->splitK == 1 && e->core == d->core && e->bm == d->bm && e->bn == d->bn &&
                 e->p1 == d->p1 && e->p2 == d->p2 && (pass == 1 || e->bk == d->bk))
                 return i;
         }

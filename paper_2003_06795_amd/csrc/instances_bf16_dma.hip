@@ -54,7 +54,7 @@ static void launch_bf16_dma(const GemmParams &p, int grid, int variant, hipStrea
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_bf16_dma<F, BM, BN, BK, WM, WN, STAGES, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0)>;
+    if constexpr ((id) % kShards == SHARD && compiled_bf16(id)) table[id] = &launch_bf16_dma<F, BM, BN, BK, WM, WN, STAGES, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0)>;
 #include "instances.def"
 #undef KS_BF16_INSTANCE
 }

@@ -60,7 +60,7 @@ static void launch_f32(const GemmParams &p, int grid, int variant, hipStream_t s
 template <int SHARD>
 static void fill(LaunchFn *table) {
 #define KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, KW) \
-    if constexpr ((id) % kShards == SHARD) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0), KW>;
+    if constexpr ((id) % kShards == SHARD && compiled_f32(id)) table[id] = &launch_f32<CORE_##CORE, BM, BN, BK, P1, P2, ((SPLITK) == 0 ? 2 : (SPLITK) > 1 ? 1 : 0), KW>;
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, 1)
 #include "instances.def"
 #undef KS_F32_INSTANCE

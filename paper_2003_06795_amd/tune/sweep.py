@@ -6,7 +6,14 @@ Each (workload, kernel) cell is timed inside the library (ks_time_gemm: HIP even
 back-to-back launches on the stream) with `--warmup` untimed launches and `--iters` samples whose
 repetition count is chosen so a sample lasts at least `--min-sample-us`; the median per-launch
 time is recorded.  Buffers are reused across launches (hot caches).  The CSV is append-only and
-keyed by (config, row, kernel): re-running skips cells already present.
+keyed by (config, row, kernel): re-running skips cells already present; `--retime` with `--kernels`
+drops the stored cells of those kernels first (after a kernel's code has changed).
+
+Before a cell is timed its first launch is checked: sampled entries of its output must agree with
+those of the row's reference member (the first kernel of the family that needs no workspace, whose
+own results the parity tests pin) within twice the stated accuracy bound.  A cell that fails is
+recorded as unusable (1e9 ms, check = fail), so a kernel that computes something else can never win
+a row of the table.
 """
 import argparse
 import csv
@@ -21,7 +28,9 @@ import workloads as wl
 from .. import binding as ks
 
 FIELDS = ["config", "row", "dtype", "transA", "transB", "M", "N", "K", "batch", "kernel",
-          "median_ms", "min_ms", "iters", "reps"]
+          "median_ms", "min_ms", "iters", "reps", "check"]
+REFERENCE_KERNEL = {"f32": 22, "bf16": 5}       # LDS-staged MFMA members without split-K
+CHECK_SAMPLES = 4096
 
 
 def rows_of(config, limit=None, seed=0):
@@ -90,6 +99,40 @@ class Buffers:
         self.strides = (M * K, K * N, M * N) if batch > 1 else (0, 0, 0)
 
 
+class Checker:
+    """First-launch check of a row: the reference member's output on sampled entries."""
+
+    def __init__(self, dtype, tA, tB, M, N, K, batch, alpha, beta, buf):
+        self.dt = ks.F32 if dtype == "f32" else ks.BF16
+        lda, ldb = (M if tA else K), (K if tB else N)
+        sA, sB, sC = buf.strides
+        self.head = (tA, tB, M, N, K, alpha, buf.A, lda, buf.B, ldb, beta)
+        self.tail = (N, batch, sA, sB, sC)
+        self.C0 = buf.C.clone()
+        n = buf.C.numel()
+        g = torch.Generator(device="cuda")
+        g.manual_seed(12345)
+        self.idx = torch.randint(0, n, (min(CHECK_SAMPLES, n),), generator=g, device="cuda")
+        self.idx[0], self.idx[-1] = 0, n - 1
+        self.scratch = torch.empty_like(buf.C)
+        self.ref = self.sample(REFERENCE_KERNEL[dtype])
+        # twice the stated bound (both sides carry it), values drawn from [-1, 1) or N(0,1)/sqrt(K)
+        amax = float(buf.A.abs().max()) * float(buf.B.abs().max())
+        rel = 1e-5 * K if dtype == "f32" else 1e-2 * np.sqrt(max(K, 1))
+        self.tol = 2.0 * (abs(alpha) * rel * amax + 1e-6 * abs(beta) * float(self.C0.abs().max())) + 1e-30
+
+    def sample(self, kid):
+        self.scratch.copy_(self.C0)
+        fn = ks.gemm_f32_with_kernel if self.dt == ks.F32 else ks.gemm_bf16_with_kernel
+        fn(kid, *self.head, self.scratch, *self.tail)
+        return self.scratch[self.idx].clone()
+
+    def ok(self, kid):
+        got = self.sample(kid)
+        err = float((got - self.ref).abs().max())
+        return bool(torch.isfinite(got).all()) and err <= self.tol
+
+
 def time_cell(dtype, kid, tA, tB, M, N, K, batch, alpha, beta, buf, warmup, iters, min_sample_us,
               max_cell_ms):
     lda, ldb, ldc = (M if tA else K), (K if tB else N), N
@@ -110,6 +153,9 @@ def main(argv=None):
     ap.add_argument("--out", required=True)
     ap.add_argument("--limit", type=int, default=None, help="config 3: size of the seeded subsample")
     ap.add_argument("--kernels", default=None, help="comma list of kernel ids (default: all)")
+    ap.add_argument("--retime", action="store_true",
+                    help="with --kernels: drop the stored cells of those kernels of this config and time them again")
+    ap.add_argument("--no-check", action="store_true", help="skip the first-launch check of every cell")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--min-sample-us", type=float, default=100.0)
@@ -121,16 +167,30 @@ def main(argv=None):
 
     rows = rows_of(a.config, a.limit)
     done = set()
+    fields = FIELDS
     if os.path.exists(a.out):
         with open(a.out) as f:
-            for r in csv.DictReader(f):
-                done.add((int(r["config"]), int(r["row"]), int(r["kernel"])))
+            rd = csv.DictReader(f)
+            fields = rd.fieldnames or FIELDS           # an older table without the check column keeps its layout
+            kept = list(rd)
+        if a.retime and a.kernels:
+            drop = {int(k) for k in a.kernels.split(",")}
+            kept = [r for r in kept if not (int(r["config"]) == a.config and int(r["kernel"]) in drop)]
+            tmp = a.out + ".tmp"
+            with open(tmp, "w", newline="") as f:
+                w = csv.DictWriter(f, fields)
+                w.writeheader()
+                w.writerows(kept)
+            os.replace(tmp, a.out)
+        for r in kept:
+            done.add((int(r["config"]), int(r["row"]), int(r["kernel"])))
     os.makedirs(os.path.dirname(os.path.abspath(a.out)), exist_ok=True)
     new = not os.path.exists(a.out)
     out = open(a.out, "a", newline="")
-    wr = csv.DictWriter(out, FIELDS)
+    wr = csv.DictWriter(out, fields, extrasaction="ignore")
     if new:
         wr.writeheader()
+    failed = 0
     ws = None
     t0 = time.time()
     last = t0
@@ -144,6 +204,7 @@ def main(argv=None):
             print("[sweep] skip row %d (%d x %d x %d): too large" % (ri, M, N, K), flush=True)
             continue
         buf = Buffers(dtype, M, N, K, batch, seed=1000 * a.config + ri)
+        chk = None if a.no_check else Checker(dtype, tA, tB, M, N, K, batch, alpha, beta, buf)
         for kid in kids:
             need = ks.workspace_bytes_needed(dt, kid, M, N, batch)
             if need > a.max_workspace_gib * 2 ** 30:
@@ -156,19 +217,28 @@ def main(argv=None):
                 ws = None
                 ws = torch.empty(need // 4 + 1, dtype=torch.float32, device="cuda")
                 ks.set_workspace(ws)
+            if chk is not None and not chk.ok(kid):
+                failed += 1
+                print("[sweep] CHECK FAILED config %d row %d kernel %d (%d x %d x %d, %d%d): recorded unusable"
+                      % (a.config, ri, kid, M, N, K, tA, tB), flush=True)
+                wr.writerow(dict(config=a.config, row=ri, dtype=dtype, transA=tA, transB=tB, M=M, N=N, K=K,
+                                 batch=batch, kernel=kid, median_ms="1e9", min_ms="1e9", iters=0, reps=0,
+                                 check="fail"))
+                continue
             med, mn, n, reps = time_cell(dtype, kid, tA, tB, M, N, K, batch, alpha, beta, buf,
                                          a.warmup, a.iters, a.min_sample_us, a.max_cell_ms)
             wr.writerow(dict(config=a.config, row=ri, dtype=dtype, transA=tA, transB=tB, M=M, N=N, K=K,
                              batch=batch, kernel=kid, median_ms="%.6g" % med, min_ms="%.6g" % mn,
-                             iters=n, reps=reps))
+                             iters=n, reps=reps, check="ok" if chk is not None else ""))
         out.flush()
-        del buf
+        del buf, chk
         if time.time() - last > 20:
             last = time.time()
             print("[sweep] config %d: %d / %d rows, %.0f s" % (a.config, n_row + 1, len(rows), last - t0),
                   flush=True)
     out.close()
-    print("[sweep] done: %d rows in %.0f s -> %s" % (len(rows), time.time() - t0, a.out), flush=True)
+    print("[sweep] done: %d rows in %.0f s -> %s; cells that failed the check: %d"
+          % (len(rows), time.time() - t0, a.out, failed), flush=True)
     return 0
 
 

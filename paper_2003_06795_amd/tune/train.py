@@ -79,6 +79,27 @@ def split_rows(rows):
     return tr, te
 
 
+LAYOUTS_PER_SHAPE = {2: 4, 7: 4, 6: 2, 8: 2, 5: 2}      # rows of one shape are consecutive in these configs
+
+
+def validation_split(rows, tr, fraction=0.2, seed=0x5a17):
+    """Carves a validation set out of the TRAINING rows, by shape (the layouts of a shape stay
+    together), seeded: hyper-parameters (leaf limits, rows per classifier leaf) are chosen on it, so
+    that the held-out test rows are looked at once, for the final number.  -> (fit mask, validation mask)"""
+    groups = {}
+    for i, r in enumerate(rows):
+        if tr[i]:
+            groups.setdefault((r["config"], r["row"] // LAYOUTS_PER_SHAPE.get(r["config"], 1)), []).append(i)
+    keys = sorted(groups)
+    perm = np.random.default_rng([seed, len(keys)]).permutation(len(keys))
+    n_val = int(round(fraction * len(keys)))
+    fit_m = np.zeros(len(rows), dtype=bool)
+    val_m = np.zeros(len(rows), dtype=bool)
+    for j, k in enumerate(perm):
+        (val_m if j < n_val else fit_m)[groups[keys[int(k)]]] = True
+    return fit_m, val_m
+
+
 def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted):
     Ph = ks.tune_normalise(Ptr)
     kept, reg = ks.tune_prune_tree(Xtr, Ph, n_kept)
@@ -153,6 +174,35 @@ def emit_table(trees):
         f.write("\n".join(lines) + "\n")
 
 
+KEPT_INC = os.path.join(os.path.dirname(HERE), "csrc", "kept_set.inc")
+BRING_UP_F32 = [0, 2, 4, 6]          # the four first-configuration tiles stay in every build
+
+
+def emit_kept_set(trees):
+    """csrc/kept_set.inc: the members a pruned build compiles = the leaves of the deployed trees
+    (plus the four bring-up tiles)."""
+    kept = {dt: sorted({int(n["value"]) for n in t if n["feature"] < 0}) for dt, t in trees.items()}
+    # a kept member with a fixed split needs its twin without split: ks_gemm_* runs that one when no
+    # workspace (or too small a one) is registered
+    for dt, code in (("f32", ks.F32), ("bf16", ks.BF16)):
+        infos = [ks.kernel_info(code, i) for i in range(ks.num_kernels(code))]
+        same = lambda a, b: all(a[k] == b[k] for k in ("core", "bm", "bn", "wm", "wn", "tm", "tn", "k_waves"))
+        for i in list(kept[dt]):
+            if infos[i]["split_k"] > 1:
+                twins = [j for j, e in enumerate(infos) if e["split_k"] == 1 and same(e, infos[i])]
+                twins.sort(key=lambda j: (infos[j]["bk"] != infos[i]["bk"], j))
+                if twins and twins[0] not in kept[dt]:
+                    kept[dt].append(twins[0])
+        kept[dt].sort()
+    f32 = sorted(set(kept["f32"]) | set(BRING_UP_F32))
+    lines = ["// Kernel ids a pruned build (-DKS_KEPT_ONLY) compiles: the leaves of the deployed trees and the",
+             "// four bring-up tiles.  Written by paper_2003_06795_amd/tune/train.py with selector_table.inc; do not edit.",
+             "#define KS_KEPT_F32 {" + ", ".join(str(i) for i in f32) + "}",
+             "#define KS_KEPT_BF16 {" + ", ".join(str(i) for i in kept["bf16"]) + "}"]
+    with open(KEPT_INC, "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
 def tree_to_json(tree):
     return [[int(n["feature"]), int(n["left"]), int(n["right"]), int(n["value"]), int(n["threshold"])]
             for n in tree]
@@ -179,6 +229,10 @@ def main(argv=None):
                     help="> 0: rows with batch > 1 are pruned and classified on their own with this leaf "
                          "limit, and the two trees are joined under a root that compares the batch count")
     ap.add_argument("--all-rows", action="store_true", help="train on every row (no held-out set)")
+    ap.add_argument("--choose-by-validation", action="store_true",
+                    help="choose --n-kept (among 4, 5, 6, 8, 12, 15), --n-kept-batched (4, 8; only if given > 0) and "
+                         "--min-samples-leaf (1, 4, 8) on a validation split of the training shapes, then refit on "
+                         "all training rows; the test rows are scored once, with the chosen setting")
     ap.add_argument("--emit", action="store_true", help="write tree JSON + csrc/selector_table.inc")
     ap.add_argument("--report", default=None)
     a = ap.parse_args(argv)
@@ -196,10 +250,36 @@ def main(argv=None):
         tr = te = np.ones(len(rows), dtype=bool)
     else:
         tr, te = split_rows(rows)
+    if a.choose_by_validation:
+        fit_m, val_m = validation_split(rows, tr)
+        trials = []
+        for n in (4, 5, 6, 8, 12, 15):
+            for nb in ((4, 8) if a.n_kept_batched > 0 else (0,)):
+                for msl in (1, 4, 8):
+                    if nb > 0:
+                        kept, _, tree = fit_by_regime(X[fit_m], P[fit_m], n, nb, a.max_depth, msl, a.weighted)
+                    else:
+                        kept, _, tree = fit(X[fit_m], P[fit_m], n, a.max_depth, msl, a.weighted)
+                    ev = evaluate(tree, kept, X[val_m], P[val_m], F[val_m])
+                    trials.append(dict(n_kept=n, n_kept_batched=nb, min_samples_leaf=msl, kernels=len(kept),
+                                       validation_selector=ev["selector"], validation_achievable=ev["achievable"]))
+        # the fewest kernels among the settings within 0.002 of the best validation score (a smaller
+        # library is what pruning is for); the better score on ties
+        top = max(t["validation_selector"] for t in trials)
+        best = min((t for t in trials if t["validation_selector"] >= top - 0.002),
+                   key=lambda t: (t["kernels"], -t["validation_selector"]))
+        print("chosen on %d validation rows (fit on %d): n_kept %d, n_kept_batched %d, min_samples_leaf %d "
+              "(validation selector %.4f)" % (int(val_m.sum()), int(fit_m.sum()), best["n_kept"],
+                                              best["n_kept_batched"], best["min_samples_leaf"],
+                                              best["validation_selector"]))
+        a.n_kept, a.n_kept_batched, a.min_samples_leaf = best["n_kept"], best["n_kept_batched"], best["min_samples_leaf"]
     report = dict(dtype=a.dtype, timings=[os.path.relpath(t) for t in a.timings], rows=len(rows),
                   train_rows=int(tr.sum()), test_rows=int(te.sum()), features=a.features,
                   max_depth=a.max_depth, min_samples_leaf=a.min_samples_leaf, weighted=a.weighted,
                   n_kept_batched=a.n_kept_batched, sweep=[])
+    if a.choose_by_validation:
+        report["validation"] = dict(fit_rows=int(fit_m.sum()), validation_rows=int(val_m.sum()), trials=trials,
+                                    chosen=best)
     chosen_fit = None
     for n in sorted({4, 5, 6, 8, 15, a.n_kept}):
         if a.n_kept_batched > 0:
@@ -239,6 +319,7 @@ def main(argv=None):
             else:
                 trees[dt] = tree_from_json([[-1, -1, -1, default, 0]])
         emit_table(trees)
+        emit_kept_set(trees)
         print("wrote %s (rebuild the library to deploy it)" % os.path.relpath(TABLE_INC))
     if a.report:
         with open(a.report, "w") as f:

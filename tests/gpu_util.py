@@ -11,6 +11,10 @@ GEMM = {"f32": ks.gemm_f32, "bf16": ks.gemm_bf16, "f16": ks.gemm_f16}
 GEMM_K = {"f32": ks.gemm_f32_with_kernel, "bf16": ks.gemm_bf16_with_kernel, "f16": ks.gemm_f16_with_kernel}
 
 
+GUARD = 64                  # canary floats kept in front of and behind every output buffer
+CANARY = -7777.25
+
+
 class DeviceProblem:
     def __init__(self, p):
         self.p = p
@@ -23,9 +27,15 @@ class DeviceProblem:
         self.C0 = torch.from_numpy(p.C0 if p.C0.size else np.zeros(1, np.float32)).to(dev)
 
     def run(self, kernel_id=None, C=None):
-        """Returns the flat C buffer after the call as numpy (same length as p.C0)."""
+        """Returns the flat C buffer after the call as numpy (same length as p.C0).  The output the
+        library sees sits between two runs of canary values, which must come back untouched."""
         p = self.p
-        C = self.C0.clone() if C is None else C
+        guarded = None
+        if C is None:
+            n = self.C0.numel()
+            guarded = torch.full((n + 2 * GUARD,), CANARY, dtype=torch.float32, device=self.C0.device)
+            guarded[GUARD:GUARD + n] = self.C0
+            C = guarded[GUARD:GUARD + n]
         args = (p.transA, p.transB, p.M, p.N, p.K, p.alpha, self.A, p.lda, self.B, p.ldb, p.beta, C,
                 p.ldc, p.batch, p.strideA, p.strideB, p.strideC)
         if kernel_id is None:
@@ -33,6 +43,9 @@ class DeviceProblem:
         else:
             GEMM_K[p.dtype](kernel_id, *args)
         torch.cuda.synchronize()
+        if guarded is not None:
+            edges = torch.cat([guarded[:GUARD], guarded[GUARD + self.C0.numel():]])
+            assert bool((edges == CANARY).all()), "kernel %s wrote outside the output buffer" % (kernel_id,)
         return C.cpu().numpy()[:p.C0.size]
 
 

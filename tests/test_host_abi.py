@@ -50,7 +50,8 @@ def test_registry_has_64_fp32_kernels_with_dense_ids():
                 f = 32 if ki["core_name"] == "mfma32" else 16
                 assert ki["wm"] == ki["tm"] * f and ki["wn"] == ki["tn"] * f
                 assert ki["threads"] == 64 * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"]) * ki["k_waves"]
-            key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"], ki["k_waves"])
+            key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"], ki["k_waves"],
+                       ki["lds_bytes"])       # LDS stages are a parameter of the 16-bit members
             assert key not in seen, "duplicate instantiation %s" % (key,)
             seen.add(key)
     with pytest.raises(ks.KsError):
@@ -133,8 +134,8 @@ def test_workspace_bytes():
     for i in range(ks.num_kernels(ks.BF16)):
         ki = ks.kernel_info(ks.BF16, i)
         got = ks.workspace_bytes_needed(ks.BF16, i, 100, 50, 2)
-        if ki["split_k"] == 0:                  # chosen per call: at most 64 partitions
-            assert got % (2 * 100 * 50 * 4) == 0 and got <= 64 * 2 * 100 * 50 * 4
+        if ki["split_k"] == 0:                  # chosen per call: at most 256 partitions (16-bit members)
+            assert got % (2 * 100 * 50 * 4) == 0 and got <= 256 * 2 * 100 * 50 * 4
         else:
             assert got == (0 if ki["split_k"] == 1 else ki["split_k"] * 2 * 100 * 50 * 4)
 

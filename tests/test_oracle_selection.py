@@ -217,3 +217,38 @@ def test_sklearn_agrees_on_regression_error_and_classifier_partition():
     # same partition of the training rows into leaves (ids differ)
     pairs = set(zip(ours_leaf.tolist(), ref_leaf.tolist()))
     assert len(pairs) == len(set(ours_leaf.tolist())) == len(set(ref_leaf.tolist()))
+
+
+def test_regime_composition_recovers_a_planted_two_regime_table():
+    """prune_and_train_by_regime pinned by a table built from a known rule: single GEMMs (batch 1)
+    prefer configuration 2 up to M = 100 and configuration 5 above, batched ones always prefer 7.
+    The joined selector must be a root 'batch <= 1' over a one-split tree and a single leaf, keep
+    exactly {2, 5, 7}, answer unseen rows by the rule, and a pooled tree with the same total leaf
+    budget spent on the many single rows must be able to lose the batched regime's choice."""
+    r = np.random.default_rng(5)
+    n = 260
+    M = r.integers(8, 400, n)
+    batch = np.where(np.arange(n) % 13 == 0, 1024, 1)          # few batched rows
+    X = np.stack([M, r.integers(8, 400, n), r.integers(8, 400, n), batch], axis=1).astype(np.int64)
+    P = 0.1 + 0.05 * r.random((n, 9))
+    rule = np.where(batch > 1, 7, np.where(M <= 100, 2, 5))
+    P[np.arange(n), rule] = 1.0
+    out = sel.prune_and_train_by_regime(X, P, 2, 1, batch_feature=3)
+    assert out["kept"] == [2, 5, 7]
+    root = out["selector"][0]
+    assert (root["feature"], root["threshold"]) == (3, 1)
+    single_root = out["selector"][root["left"]]
+    assert single_root["feature"] == 0 and 93 <= single_root["threshold"] <= 107
+    assert out["selector"][root["right"]]["feature"] == -1 and out["selector"][root["right"]]["label"] == 7
+    Xnew = np.array([[50, 9, 9, 1], [399, 9, 9, 1], [50, 9, 9, 4096], [399, 300, 20, 256]], dtype=np.int64)
+    assert sel.predict_labels(out["selector"], Xnew).tolist() == [2, 5, 7, 7]
+    # the answers for single GEMMs do not depend on what the batched rows look like
+    P2 = P.copy()
+    P2[batch > 1] = P[batch > 1][:, ::-1]
+    out2 = sel.prune_and_train_by_regime(X, P2, 2, 1, batch_feature=3)
+    single = X[batch == 1]
+    assert np.array_equal(sel.predict_labels(out2["selector"], single), sel.predict_labels(out["selector"], single))
+    # one regime only: the plain pipeline
+    only = sel.prune_and_train_by_regime(X[batch == 1], P[batch == 1], 2, 1, batch_feature=3)
+    plain = sel.prune_and_train(X[batch == 1], P[batch == 1], 2)
+    assert only["kept"] == plain["kept"] == [2, 5]

@@ -185,3 +185,29 @@ def test_trees_per_regime_join_under_a_batch_comparison():
         ks.set_selector(ks.F32, None)
     # a table with one regime only falls back to the plain fit
     assert train.fit_by_regime(X[~batched], P[~batched], 6, 3, 12, 1, False)[2].tobytes() == t1.tobytes()
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_regime_pipeline_matches_the_oracle_composition(seed):
+    """train.fit_by_regime (the deployed fp32 pipeline: one pruning tree and one classifier per
+    regime under a batch comparison) against oracle.selection.prune_and_train_by_regime: same kept
+    set, structurally the same joined tree, same answers on unseen rows."""
+    from paper_2003_06795_amd.tune import train
+    X, P = table(320, 16, seed)
+    r = np.random.default_rng(seed)
+    batched = r.random(len(X)) < 0.3
+    X = X.copy()
+    X[batched, train.BATCH_FEATURE] = r.choice([256, 1024, 4096], int(batched.sum()))
+    P = P.copy()
+    P[batched, 7] += 2e12
+    P[batched, 9] += 1e12 * (X[batched, 0] > 256)
+    Xtr, Ptr, Xte = X[:240], P[:240], X[240:]
+    for (n1, n2, msl) in ((6, 3, 1), (15, 4, 1), (8, 8, 4)):
+        kept, _, tree = train.fit_by_regime(Xtr, Ptr, n1, n2, 12, msl, False)
+        ref = sel.prune_and_train_by_regime(Xtr, Ptr, n1, n2, train.BATCH_FEATURE, 12, msl)
+        assert kept.tolist() == ref["kept"]
+        same_tree(tree, ref["selector"], lambda nd: nd["label"])
+        assert np.array_equal(ks.tune_predict(tree, Xte), sel.predict_labels(ref["selector"], Xte))
+    # a planted case the composition must get right: the batched rows' best configuration is kept
+    # although no single GEMM prefers it
+    assert 7 in ref["kept"] and 7 not in ref["parts"][0]["kept"]
