@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg5] [--single-launch]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg5|fp32_large] [--single-launch]
 
 A step is one pass of the deployed library over the workload: for every (shape, layout) row,
 ks_select picks a kernel and ks_gemm_* runs it (inputs resident in HBM).  The default workload is
@@ -358,7 +358,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5", "fp32_large"])
     ap.add_argument("--single-launch", action="store_true", help="one launch per sample (profiler runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the reports measured after the timed region")
@@ -453,9 +453,11 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": wall / a.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": ("fp32 tuning set: 200 log-uniform shapes in [16,4096]^3 (seed 1) x 4 layouts, "
-                                "selected kernel per row" if a.workload == "cfg2" else
-                                "bf16 large/skinny set: 7 shapes x {NN,NT}, selected kernel per row"),
+        "config": {"workload": {"cfg2": "fp32 tuning set: 200 log-uniform shapes in [16,4096]^3 (seed 1) x 4 layouts, "
+                                        "selected kernel per row",
+                                "cfg5": "bf16 large/skinny set: 7 shapes x {NN,NT}, selected kernel per row",
+                                "fp32_large": "fp32 4096^3 in four layouts and three large im2col rows, selected kernel "
+                                              "per row"}[a.workload],
                    "rows": len(rows), "kernels_used": len(set(chosen)),
                    "rows_that_split_k": int(sum(p["split_k"] > 1 for p in plans)),
                    "launches_per_step": int(sum(1 + SAMPLES * r for r in reps)),

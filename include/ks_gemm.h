@@ -83,6 +83,8 @@ typedef struct {
                             slice and wave tile for core KS_CORE_KSLICE, one complete group of waves
                             (threads / k_waves lanes, its own LDS stages) per slice for the LDS-staged
                             MFMA cores; 1 = none */
+    int32_t band_rows;   /* tile order of a one-dimensional launch: tiles are walked in bands of this many
+                            tile rows, column-major inside a band (which tiles share an XCD's L2) */
     int32_t available;   /* 1: compiled into this library; 0: pruned away (a library built with only the
                             kept set of the deployed trees, Section III, holds the kept members and the
                             four bring-up tiles; forcing an absent member returns KS_ERR_UNSUPPORTED) */

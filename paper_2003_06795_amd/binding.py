@@ -24,7 +24,7 @@ FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "mi
 class KernelInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("id", "dtype", "core", "bm", "bn", "bk", "wm", "wn", "tm", "tn", "threads",
-                 "split_k", "lds_bytes", "k_waves", "available")]
+                 "split_k", "lds_bytes", "k_waves", "band_rows", "available")]
 
     def as_dict(self):
         d = {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -51,11 +51,14 @@ const InstanceDesc kF32[kNumF32] = {
 };
 
 const InstanceDesc kBf16[kNumBf16] = {
-#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK)                           \
+#define KS_BF16_INSTANCE_BAND(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK, BAND)                \
     {id, (F) == 16 ? KS_CORE_MFMA16 : KS_CORE_MFMA32, BM, BN, BK, WM, WN, 64 * (BM / WM) * (BN / WN), \
-     SPLITK, STAGES * BK * (BM + BN) * 2, 1},
+     SPLITK, STAGES * BK * (BM + BN) * 2, 1, BAND},
+#define KS_BF16_INSTANCE(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK) \
+    KS_BF16_INSTANCE_BAND(id, F, BM, BN, BK, WM, WN, STAGES, SPLITK, 8)
 #include "instances.def"
 #undef KS_BF16_INSTANCE
+#undef KS_BF16_INSTANCE_BAND
 };
 
 LaunchFn g_f32[kNumF32];
@@ -327,6 +330,7 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
                    ? 1
                    : 0;
     p.tilesPerWG = 1;
+    p.bandRows = d->band;
     if (dtype == KS_F32 && !p.grid3d && p.splitK == 1 && f32_multi_tile(d->core, d->bm, d->bn, d->p1, d->p2, d->kw)) {
         p.tilesPerWG = g_tilesPerWG > 0 ? g_tilesPerWG : multi_tiles(d, grid64, K);
         grid64 = (grid64 + p.tilesPerWG - 1) / p.tilesPerWG;
@@ -428,6 +432,7 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     out->threads = d->threads;
     out->split_k = d->splitK;
     out->lds_bytes = d->ldsBytes;
+    out->band_rows = d->band;
     std::call_once(g_once, init_tables);
     out->available = (dtype == KS_F32 ? g_f32[kernel_id] : g_bf16[kernel_id]) != nullptr ? 1 : 0;
     return KS_OK;

@@ -23,6 +23,8 @@ struct GemmParams {
     int grid3d;                      // 1: launched as (tilesN, tilesM, batch*splitK) work-groups
     int tilesPerWG;                  // consecutive logical tiles one work-group walks (members that
                                      // support it; 1 everywhere else and on 3-D launches)
+    int bandRows;                    // tile rows per band of the one-dimensional tile order (8 unless the
+                                     // member says otherwise)
     int out16;                       // 1: C holds bf16 (2-byte elements; ldc in elements); strideC is
                                      //    then 0 and the batch stride, in elements, is strideC16
     long long strideC16;
@@ -75,8 +77,9 @@ struct TileCoord {
 
 // MI355X has 8 XCDs with private L2s and hands consecutive work-group ids to them round-robin.
 // Renumber so that each XCD owns one contiguous run of logical tile ids, then walk tiles in
-// bands of 8 tile-rows (column-major inside a band) so the tiles resident on one XCD form a
-// compact block that shares A row-panels and B column-panels in that XCD's L2.
+// bands of a few tile-rows (8 by default; a tunable axis of the 16-bit family), column-major inside
+// a band, so the tiles resident on one XCD form a compact block that shares A row-panels and B
+// column-panels in that XCD's L2.
 // Small grids (where a handful of integer divisions is a visible part of a 3 us kernel and L2
 // locality is not at stake) are launched three-dimensional instead and read their tile directly.
 __device__ __forceinline__ unsigned logical_of_block() {
@@ -86,17 +89,18 @@ __device__ __forceinline__ unsigned logical_of_block() {
 }
 
 // tile with logical id `logical` of a one-dimensional launch: units (batch item, K partition) in
-// order, inside a unit bands of 8 tile-rows walked column-major
+// order, inside a unit bands of p.bandRows tile-rows walked column-major
 __device__ __forceinline__ TileCoord tile_of_logical(const GemmParams &p, unsigned logical) {
     const unsigned per = (unsigned)p.tilesM * (unsigned)p.tilesN;
     const unsigned unit = logical / per, t = logical - unit * per;
     TileCoord c;
     c.batch = (int)(unit / (unsigned)p.splitK);
     c.split = (int)(unit - (unsigned)c.batch * (unsigned)p.splitK);
-    const unsigned band = 8u * (unsigned)p.tilesN;
+    const unsigned h = (unsigned)p.bandRows;
+    const unsigned band = h * (unsigned)p.tilesN;
     const unsigned g = t / band, in = t - g * band;
-    const unsigned first = g * 8u;
-    const unsigned rows = ((unsigned)p.tilesM - first) < 8u ? ((unsigned)p.tilesM - first) : 8u;
+    const unsigned first = g * h;
+    const unsigned rows = ((unsigned)p.tilesM - first) < h ? ((unsigned)p.tilesM - first) : h;
     c.tn = (int)(in / rows);
     c.tm = (int)(first + (in - (unsigned)c.tn * rows));
     return c;

@@ -9,6 +9,7 @@ typedef void (*LaunchFn)(const GemmParams &p, int grid, int variant, hipStream_t
 
 struct InstanceDesc {
     int id, core, bm, bn, bk, p1, p2, threads, splitK, ldsBytes, kw;
+    int band = 8;        // tile rows per band of the one-dimensional tile order
 };
 
 // Pruned library (paper Sections I and II-B: every instantiation costs binary size and build time,
@@ -33,7 +34,7 @@ constexpr bool compiled_bf16(int) { return true; }
 #endif
 
 constexpr int kNumF32 = 64;
-constexpr int kNumBf16 = 40;
+constexpr int kNumBf16 = 44;
 constexpr int kShards = 16;
 
 }  // namespace ks

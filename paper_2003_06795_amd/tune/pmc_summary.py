@@ -35,7 +35,7 @@ def main(fetch_csv, write_csv, workload):
     wf = (CALIB_BYTES / 1024.0) / (sum(w[ck]) / len(w[ck]))
     out = dict(workload=workload,
                command=("rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o p -- python3 bench.py "
-                        "--workload %s --steps 1 --warmup 0 --no-cpu --no-extra  (and the same with "
+                        "--workload %s --steps 1 --warmup 0 --no-cpu --no-extra --single-launch  (and the same with "
                         "--pmc WRITE_SIZE); python -m paper_2003_06795_amd.tune.pmc_summary "
                         "<fetch>/p_counter_collection.csv <write>/p_counter_collection.csv %s" % (workload, workload)),
                calibration=dict(kernel=short(ck), bytes_each_way=CALIB_BYTES,

@@ -66,6 +66,10 @@ def rows_of(config, limit=None, seed=0):
     elif config == 7:
         for i, (s, tA, tB, M, N, K, b) in enumerate(wl.config2_extra_rows()):
             out.append((i, "f32", tA, tB, M, N, K, b, 1.0, 0.0))
+    elif config == 12:
+        # large fp32 shapes (all three dimensions 2048 .. 8192): training only
+        for i, (s, tA, tB, M, N, K, b) in enumerate(wl.large_fp32_rows()):
+            out.append((i, "f32", tA, tB, M, N, K, b, 1.0, 0.0))
     elif config == 11:
         # more batched small shapes (other dimensions and batch sizes): training only
         for i, (M, N, K, b) in enumerate(wl.config4_extra_rows()):

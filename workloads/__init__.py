@@ -203,6 +203,22 @@ def config2_extra_rows(n=400, seed=11):
     return rows
 
 
+def large_fp32_rows(n=24, seed=16, lo=2048, hi=8192):
+    """Large fp32 GEMMs, for training the fp32 selector only (the tuning set stops at 4096 and holds
+    few shapes that are large in all three dimensions): M, N, K log-uniform in [lo, hi], multiples
+    of 64, M*N*K at most 2^37; all four layouts."""
+    r = np.random.default_rng(seed)
+    rows, s = [], 0
+    while s < n:
+        M, N, K = (int(round(np.exp(r.uniform(np.log(lo), np.log(hi))) / 64.0)) * 64 for _ in range(3))
+        if M * N * K > 2 ** 37:
+            continue
+        for tA, tB in itertools.product((0, 1), (0, 1)):
+            rows.append((s, tA, tB, M, N, K, 1))
+        s += 1
+    return rows
+
+
 def config2_split(n=200, seed=1, train_fraction=0.7):
     """Indices of the train and test shapes (shapes, not rows: the four transpose
     combinations of one shape stay on the same side)."""
