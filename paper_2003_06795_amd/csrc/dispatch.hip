@@ -190,7 +190,16 @@ __global__ void splitk_reduce4_kernel(const float *ws, float *C, long long ldc, 
          q += (long long)gridDim.x * blockDim.x) {
         const long long i = q << 2;
         floatx4 acc = *reinterpret_cast<const floatx4 *>(ws + i);
-        for (int s = 1; s < splitK; ++s) acc += *reinterpret_cast<const floatx4 *>(ws + (long long)s * per + i);
+        // partial sums are fetched eight at a time (independent loads) and added in partition order
+        int s = 1;
+        for (; s + 8 <= splitK; s += 8) {
+            floatx4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const floatx4 *>(ws + (long long)(s + u) * per + i);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; s < splitK; ++s) acc += *reinterpret_cast<const floatx4 *>(ws + (long long)s * per + i);
         const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
         floatx4 *c = reinterpret_cast<floatx4 *>(C + b * strideC + (r / N) * ldc + (r % N));
         floatx4 v = alpha * acc;
@@ -215,7 +224,15 @@ __global__ void splitk_reduce_kernel(const float *ws, float *C, long long ldc, l
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < per;
          i += (long long)gridDim.x * blockDim.x) {
         float acc = ws[i];
-        for (int s = 1; s < splitK; ++s) acc += ws[(long long)s * per + i];
+        int s = 1;
+        for (; s + 8 <= splitK; s += 8) {                 // eight independent loads, added in partition order
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = ws[(long long)(s + u) * per + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; s < splitK; ++s) acc += ws[(long long)s * per + i];
         const long long b = i / ((long long)M * N), r = i - b * (long long)M * N;
         if (out16) {
             store_bf16_out(C, b * strideC + (r / N) * ldc + (r % N), acc, alpha, beta, bias ? bias[r % N] : 0.0f);
@@ -378,8 +395,10 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
 
     if (p.splitK > 1) {
         const long long total = (long long)batch * M * N;
+        // four entries per lane once there are enough entries to fill the device that way; small
+        // outputs with many partitions run one entry per lane (same sums either way)
         const bool vec4 = !out16 && N % 4 == 0 && ldc % 4 == 0 && aligned(C, 16) && aligned(p.ws, 16) &&
-                          (batch == 1 || strideC % 4 == 0);
+                          (batch == 1 || strideC % 4 == 0) && total >= 4LL * 256 * 256;
         const long long units = vec4 ? total / 4 : total;
         const int grid = (int)((units + 255) / 256 < 1048576 ? (units + 255) / 256 : 1048576);
         if (vec4)

@@ -74,6 +74,9 @@ def split_rows(rows):
         elif r["config"] in other:
             tr[i] = r["row"] in other[r["config"]]
             te[i] = not tr[i]
+        elif r["config"] == 12:
+            # large fp32 shapes: every other shape is held out
+            tr[i], te[i] = (r["row"] // 4) % 2 == 0, (r["row"] // 4) % 2 == 1
         else:
             tr[i] = True
     return tr, te
@@ -100,9 +103,13 @@ def validation_split(rows, tr, fraction=0.2, seed=0x5a17):
     return fit_m, val_m
 
 
-def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted):
+def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted, prune=None):
+    """prune: optional boolean mask of the rows the pruning tree sees (the classifier sees all)."""
     Ph = ks.tune_normalise(Ptr)
-    kept, reg = ks.tune_prune_tree(Xtr, Ph, n_kept)
+    if prune is None or prune.all():
+        kept, reg = ks.tune_prune_tree(Xtr, Ph, n_kept)
+    else:
+        kept, reg = ks.tune_prune_tree(Xtr[prune], Ph[prune], n_kept)
     w = None
     if weighted:
         # optional, not in the paper: weight a row by what a wrong choice inside the kept set can
@@ -117,16 +124,18 @@ def fit(Xtr, Ptr, n_kept, max_depth, min_samples_leaf, weighted):
 BATCH_FEATURE = 3          # index of `batch` in the ks_features layout
 
 
-def fit_by_regime(Xtr, Ptr, n_single, n_batched, max_depth, min_samples_leaf, weighted):
+def fit_by_regime(Xtr, Ptr, n_single, n_batched, max_depth, min_samples_leaf, weighted, prune=None):
     """One pruning + classifier fit per regime (single GEMMs, batch == 1; batched ones, batch > 1),
     each with its own leaf limit, joined under a root that compares the batch count: the deployed
     selector stays one tree of nested comparisons (Section IV), but the rows of one regime no
     longer compete with the other's for the pruning tree's leaves (Section III)."""
     single = Xtr[:, BATCH_FEATURE] <= 1
+    if prune is None:
+        prune = np.ones(len(Xtr), dtype=bool)
     if single.all() or not single.any():
-        return fit(Xtr, Ptr, n_single, max_depth, min_samples_leaf, weighted)
-    k1, r1, t1 = fit(Xtr[single], Ptr[single], n_single, max_depth, min_samples_leaf, weighted)
-    k2, r2, t2 = fit(Xtr[~single], Ptr[~single], n_batched, max_depth, min_samples_leaf, weighted)
+        return fit(Xtr, Ptr, n_single, max_depth, min_samples_leaf, weighted, prune)
+    k1, r1, t1 = fit(Xtr[single], Ptr[single], n_single, max_depth, min_samples_leaf, weighted, prune[single])
+    k2, r2, t2 = fit(Xtr[~single], Ptr[~single], n_batched, max_depth, min_samples_leaf, weighted, prune[~single])
 
     def join(a, b):
         out = np.zeros(1 + len(a) + len(b), dtype=ks.TREE_DTYPE)
@@ -229,6 +238,9 @@ def main(argv=None):
                     help="> 0: rows with batch > 1 are pruned and classified on their own with this leaf "
                          "limit, and the two trees are joined under a root that compares the batch count")
     ap.add_argument("--all-rows", action="store_true", help="train on every row (no held-out set)")
+    ap.add_argument("--classifier-only-configs", default="",
+                    help="comma list of config numbers whose training rows join the classifier fit but not the "
+                         "pruning step (rows that would otherwise pull the few leaves of the pruning tree away)")
     ap.add_argument("--choose-by-validation", action="store_true",
                     help="choose --n-kept (among 4, 5, 6, 8, 12, 15), --n-kept-batched (4, 8; only if given > 0) and "
                          "--min-samples-leaf (1, 4, 8) on a validation split of the training shapes, then refit on "
@@ -250,6 +262,8 @@ def main(argv=None):
         tr = te = np.ones(len(rows), dtype=bool)
     else:
         tr, te = split_rows(rows)
+    conly = {int(c) for c in a.classifier_only_configs.split(",") if c}
+    prune_rows = np.array([r["config"] not in conly for r in rows])
     if a.choose_by_validation:
         fit_m, val_m = validation_split(rows, tr)
         trials = []
@@ -257,9 +271,10 @@ def main(argv=None):
             for nb in ((4, 8) if a.n_kept_batched > 0 else (0,)):
                 for msl in (1, 4, 8):
                     if nb > 0:
-                        kept, _, tree = fit_by_regime(X[fit_m], P[fit_m], n, nb, a.max_depth, msl, a.weighted)
+                        kept, _, tree = fit_by_regime(X[fit_m], P[fit_m], n, nb, a.max_depth, msl, a.weighted,
+                                                      prune_rows[fit_m])
                     else:
-                        kept, _, tree = fit(X[fit_m], P[fit_m], n, a.max_depth, msl, a.weighted)
+                        kept, _, tree = fit(X[fit_m], P[fit_m], n, a.max_depth, msl, a.weighted, prune_rows[fit_m])
                     ev = evaluate(tree, kept, X[val_m], P[val_m], F[val_m])
                     trials.append(dict(n_kept=n, n_kept_batched=nb, min_samples_leaf=msl, kernels=len(kept),
                                        validation_selector=ev["selector"], validation_achievable=ev["achievable"]))
@@ -276,7 +291,7 @@ def main(argv=None):
     report = dict(dtype=a.dtype, timings=[os.path.relpath(t) for t in a.timings], rows=len(rows),
                   train_rows=int(tr.sum()), test_rows=int(te.sum()), features=a.features,
                   max_depth=a.max_depth, min_samples_leaf=a.min_samples_leaf, weighted=a.weighted,
-                  n_kept_batched=a.n_kept_batched, sweep=[])
+                  n_kept_batched=a.n_kept_batched, classifier_only_configs=sorted(conly), sweep=[])
     if a.choose_by_validation:
         report["validation"] = dict(fit_rows=int(fit_m.sum()), validation_rows=int(val_m.sum()), trials=trials,
                                     chosen=best)
@@ -284,9 +299,9 @@ def main(argv=None):
     for n in sorted({4, 5, 6, 8, 15, a.n_kept}):
         if a.n_kept_batched > 0:
             kept, reg, tree = fit_by_regime(X[tr], P[tr], n, a.n_kept_batched, a.max_depth, a.min_samples_leaf,
-                                            a.weighted)
+                                            a.weighted, prune_rows[tr])
         else:
-            kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted)
+            kept, reg, tree = fit(X[tr], P[tr], n, a.max_depth, a.min_samples_leaf, a.weighted, prune_rows[tr])
         ev_tr, ev_te = evaluate(tree, kept, X[tr], P[tr], F[tr]), evaluate(tree, kept, X[te], P[te], F[te])
         per_cfg = {}
         for cfg in sorted({r["config"] for r in rows}):
