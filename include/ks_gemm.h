@@ -289,6 +289,20 @@ int ks_calibration_copy(void *dst_device, const void *src_device, size_t bytes, 
 int ks_mfma_sustained(int dtype, const void *operands_device, size_t bytes, int rounds, void *stream,
                       double *tflops_out, double *mhz_out);
 
+/* Measurement aid: the two-group 256 x 256 x 64 bf16 kernel on an NT problem (A: M x K, B: N x K,
+ * both K-contiguous bf16 device buffers; C: M x N fp32 device buffer that is overwritten) with one of
+ * its data paths left out, to read off what each path costs on given operand values:
+ *   mode 0  the kernel as ks_gemm_bf16 runs it (C is the product)
+ *   mode 1  no direct-to-LDS global loads after the first two K-steps
+ *   mode 2  no LDS fragment reads after the first two K-steps
+ *   mode 3  neither (MFMAs, barriers and the C write only)
+ * For modes 1-3 the MFMAs run on the first K-steps' operands over and over: C is NOT a GEMM
+ * result.  M, N multiples of 256, K a multiple of 64 and at least 128.  Two untimed launches, then
+ * `iters` launches timed with HIP events one by one; ms_out[0 .. iters-1] (host) receives the
+ * milliseconds.  Synchronises. */
+int ks_bf16_ablation(int mode, const uint16_t *A_device, const uint16_t *B_device, float *C_device,
+                     int64_t M, int64_t N, int64_t K, void *stream, int iters, float *ms_out);
+
 /* ---------------------------------------------------------------- workspace
  * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no
  * atomics) need split_k * batch * M * N floats of scratch.  The caller registers one device
@@ -305,6 +319,11 @@ size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N,
  * Trees are CART with integer thresholds floor(midpoint); "x <= t" goes left.  Ties: argmax ->
  * lowest index; a split replaces the current best only if its gain is larger by a relative
  * 1e-9; best-first priority ties -> earliest node.  Fully deterministic. */
+
+/* Section II-A: the performance of configuration c on workload s from its measured time,
+ * out[s][c] = 2 * M * N * K * batch / seconds[s][c] (flop/s).  sizes: rows x 4 int64 (M, N, K, batch);
+ * seconds: rows x cols, every entry positive. */
+int ks_tune_performance(const int64_t *sizes, const double *seconds, int rows, int cols, double *out);
 
 /* Section II-A: out[s][c] = perf[s][c] / max_c perf[s][c]. */
 int ks_tune_normalise(const double *perf, int rows, int cols, double *out);

@@ -60,9 +60,9 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
-    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
+    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_bf16_ablation", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_workspace", "ks_workspace_bytes_needed",
-    "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
+    "ks_tune_performance", "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
     "ks_tune_pca_variance", "ks_status_string",
 ]
@@ -101,11 +101,13 @@ def lib():
     L.ks_get_selector.argtypes = [_i, _p, _i]
     L.ks_calibration_copy.argtypes = [_p, _p, ctypes.c_size_t, _p]
     L.ks_mfma_sustained.argtypes = [_i, _p, ctypes.c_size_t, _i, _p, _p, _p]
+    L.ks_bf16_ablation.argtypes = [_i, _p, _p, _p, _i64, _i64, _i64, _p, _i, _p]
     L.ks_set_fast_path.argtypes = [_i]
     L.ks_set_tiles_per_workgroup.argtypes = [_i]
     L.ks_set_workspace.argtypes = [_p, ctypes.c_size_t]
     L.ks_workspace_bytes_needed.argtypes = [_i, _i, _i64, _i64, _i64]
     L.ks_workspace_bytes_needed.restype = ctypes.c_size_t
+    L.ks_tune_performance.argtypes = [_p, _p, _i, _i, _p]
     L.ks_tune_normalise.argtypes = [_p, _i, _i, _p]
     L.ks_tune_prune_tree.argtypes = [_p, _i, _p, _i, _i, _i, _i, _p, _p, _p]
     L.ks_tune_achievable.argtypes = [_p, _i, _i, _p, _i, _p]
@@ -308,6 +310,14 @@ def mfma_sustained(dtype, operands, nbytes=None, rounds=2000, stream=None):
     return tf.value, mhz.value
 
 
+def bf16_ablation(mode, A, B, C, M, N, K, iters=10, stream=None):
+    """Milliseconds of `iters` launches of the two-group bf16 kernel with data paths left out (mode 0-3)."""
+    out = np.zeros(iters, dtype=np.float32)
+    _check(lib().ks_bf16_ablation(int(mode), _dev(A), _dev(B), _dev(C), M, N, K, _stream(stream), int(iters),
+                                  out.ctypes.data_as(_p)), "ks_bf16_ablation")
+    return out
+
+
 def set_fast_path(enabled):
     _check(lib().ks_set_fast_path(int(bool(enabled))), "ks_set_fast_path")
 
@@ -332,6 +342,15 @@ def workspace_bytes_needed(dtype, kernel_id, M, N, batch=1):
 
 
 # ------------------------------------------------------------------------------ offline tuner (host)
+
+def tune_performance(sizes, seconds):
+    """flop/s table from (M, N, K, batch) rows and the measured seconds [rows x kernels]."""
+    z, zp = _np(sizes, np.int64)
+    t, tp = _np(seconds, np.float64)
+    out = np.empty_like(t)
+    _check(lib().ks_tune_performance(zp, tp, t.shape[0], t.shape[1], out.ctypes.data_as(_p)), "ks_tune_performance")
+    return out
+
 
 def tune_normalise(perf):
     a, p = _np(perf, np.float64)

@@ -72,7 +72,11 @@ struct PpPlan {
     }
 };
 
-template <int F, bool SPLIT, bool AKC, bool BKC, bool F16 = false>
+// ABLATE != 0 exists for measurement only (ks_bf16_ablation; the result is then not a GEMM): bit 0
+// leaves out the direct-to-LDS loads after the first two K-steps (LDS keeps their contents), bit 1
+// the LDS fragment reads after the first two K-steps (the registers keep theirs), so that the cost
+// of each data path can be read off against the full kernel on the same operand values.
+template <int F, bool SPLIT, bool AKC, bool BKC, bool F16 = false, int ABLATE = 0>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     constexpr int BM = 256, BN = 256, BK = 64, HALF = 128;
     constexpr int FM = 64 / F, FN = 32 / F;                  // fragments of a wave's 64 x 32 block
@@ -186,11 +190,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         using SC = std::integral_constant<int, S>;
         using SN = std::integral_constant<int, S ^ 1>;
         const int t1 = min(t + 1, nk - 1), t2 = min(t + 2, nk - 1);
+        const bool reads = (ABLATE & 2) == 0 || t < 2;
         // M0
-        read_a(lds_a(SC{}, I0{}));
-        read_b(lds_b(SC{}, I0{}), b0);
-        read_b(lds_b(SC{}, I1{}), b1);
-        pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave);
+        if (reads) {
+            read_a(lds_a(SC{}, I0{}));
+            read_b(lds_b(SC{}, I0{}), b0);
+            read_b(lds_b(SC{}, I1{}), b1);
+        }
+        if constexpr ((ABLATE & 1) == 0) pa1.issue(aTile + t1 * aStep, lds_a(SN{}, I1{}), wave);
         memory_slot_end();
         // C0: the wave that is issuing MFMAs goes ahead of the one issuing memory instructions
         __builtin_amdgcn_s_setprio(1);
@@ -199,10 +206,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         __builtin_amdgcn_s_setprio(0);
         slot_end();
         // M1
-        read_a(lds_a(SC{}, I1{}));
-        pa0.issue(aTile + t2 * aStep, lds_a(SC{}, I0{}), wave);
-        pb0.issue(bTile + t2 * bStep, lds_b(SC{}, I0{}), wave);
-        pb1.issue(bTile + t2 * bStep, lds_b(SC{}, I1{}), wave);
+        if (reads) read_a(lds_a(SC{}, I1{}));
+        if constexpr ((ABLATE & 1) == 0) {
+            pa0.issue(aTile + t2 * aStep, lds_a(SC{}, I0{}), wave);
+            pb0.issue(bTile + t2 * bStep, lds_b(SC{}, I0{}), wave);
+            pb1.issue(bTile + t2 * bStep, lds_b(SC{}, I1{}), wave);
+        }
         memory_slot_end();
         // C1
         __builtin_amdgcn_s_setprio(1);

@@ -5,7 +5,7 @@
 #include <mutex>
 
 #include "../../include/ks_gemm.h"
-#include "gemm_bf16.hpp"
+#include "gemm_bf16_pp.hpp"
 
 namespace ks {
 namespace {
@@ -104,4 +104,43 @@ extern "C" int ks_mfma_sustained(int dtype, const void *operands_device, size_t 
         *mhz_out = h[1] ? (double)h[0] / ((double)h[1] * 0.01) : 0.0;
     }
     return KS_OK;
+}
+
+extern "C" int ks_bf16_ablation(int mode, const uint16_t *A, const uint16_t *B, float *C, int64_t M, int64_t N,
+                                int64_t K, void *stream, int iters, float *ms_out) {
+    if (mode < 0 || mode > 3 || !A || !B || !C || !ms_out || iters < 1 || iters > 1024) return KS_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K < 128 || M % 256 || N % 256 || K % 64 || M > 65536 || N > 65536 || K > (1 << 22))
+        return KS_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(A) % 16 || reinterpret_cast<uintptr_t>(B) % 16) return KS_ERR_INVALID_ARG;
+    GemmParams p{};
+    p.A = A; p.B = B; p.C = C;
+    p.lda = K; p.ldb = K; p.ldc = N;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = 1;
+    p.tilesM = (int)(M / 256); p.tilesN = (int)(N / 256);
+    p.splitK = 1; p.kChunk = (int)K; p.grid3d = 0; p.tilesPerWG = 1; p.bandRows = 8;
+    p.alpha = 1.0f; p.beta = 0.0f;
+    const dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(512);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    (void)hipGetLastError();
+    if (hipEventCreate(&e0) != hipSuccess) return KS_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return KS_ERR_LAUNCH; }
+    int rc = KS_OK;
+    for (int it = -2; it < iters && rc == KS_OK; ++it) {             // two untimed launches first
+        if (hipEventRecord(e0, s) != hipSuccess) rc = KS_ERR_LAUNCH;
+        switch (mode) {
+            case 0: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 0>), grid, block, 0, s, p); break;
+            case 1: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 1>), grid, block, 0, s, p); break;
+            case 2: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 2>), grid, block, 0, s, p); break;
+            default: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 3>), grid, block, 0, s, p); break;
+        }
+        float ms = 0.f;
+        if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess ||
+            hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+            rc = KS_ERR_LAUNCH;
+        if (it >= 0) ms_out[it] = ms;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
 }

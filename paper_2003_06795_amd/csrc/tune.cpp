@@ -151,6 +151,21 @@ struct Grow {
 
 }  // namespace
 
+extern "C" int ks_tune_performance(const int64_t *sizes, const double *seconds, int rows, int cols, double *out) {
+    if (!sizes || !seconds || !out || rows < 0 || cols <= 0) return KS_ERR_INVALID_ARG;
+    for (int s = 0; s < rows; ++s) {
+        const int64_t *z = sizes + (size_t)s * 4;
+        if (z[0] < 0 || z[1] < 0 || z[2] < 0 || z[3] < 0) return KS_ERR_INVALID_ARG;
+        const double flops = 2.0 * (double)z[0] * (double)z[1] * (double)z[2] * (double)z[3];
+        for (int c = 0; c < cols; ++c) {
+            const double t = seconds[(size_t)s * cols + c];
+            if (!(t > 0.0)) return KS_ERR_INVALID_ARG;
+            out[(size_t)s * cols + c] = flops / t;
+        }
+    }
+    return KS_OK;
+}
+
 extern "C" int ks_tune_normalise(const double *perf, int rows, int cols, double *out) {
     if (!perf || !out || rows < 0 || cols <= 0) return KS_ERR_INVALID_ARG;
     for (int s = 0; s < rows; ++s) {

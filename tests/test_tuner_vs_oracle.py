@@ -211,3 +211,14 @@ def test_regime_pipeline_matches_the_oracle_composition(seed):
     # a planted case the composition must get right: the batched rows' best configuration is kept
     # although no single GEMM prefers it
     assert 7 in ref["kept"] and 7 not in ref["parts"][0]["kept"]
+
+
+def test_performance_table_matches_the_oracle_definition():
+    r = np.random.default_rng(9)
+    sizes = r.integers(1, 5000, (40, 4)).astype(np.int64)
+    secs = r.random((40, 7)) * 1e-3 + 1e-6
+    ours = ks.tune_performance(sizes, secs)
+    flops = 2.0 * sizes[:, 0] * sizes[:, 1] * sizes[:, 2] * sizes[:, 3]
+    assert np.array_equal(ours, sel.performance(flops, secs))
+    with pytest.raises(ks.KsError):
+        ks.tune_performance(sizes, secs * 0.0)
