@@ -353,6 +353,18 @@ int ks_tune_prune_top_n(const double *normalised, int rows, int cols, int n, int
 int ks_tune_prune_kmeans(const double *normalised, int rows, int cols, int n, int pca_dims,
                          int max_iter, int32_t *kept_out);
 
+/*   hdbscan: density-based clustering of the rows of `normalised` (core distance to the
+ *            min_samples-th nearest row, itself included; mutual reachability; minimum spanning tree;
+ *            condensed single-linkage tree with min_cluster_size; excess-of-mass selection, the root
+ *            never selected), in which the number of clusters is a result; each cluster's centroid
+ *            contributes its best configuration, rows labelled noise take no part, and with no
+ *            cluster at all the centroid of all rows is used.  labels_out (rows entries, may be NULL)
+ *            receives the cluster of every row, numbered by first member, or -1 for noise.
+ *            kept_cap: capacity of kept_out.  KS_ERR_UNSUPPORTED above about 22000 rows (the
+ *            distance matrix is dense). */
+int ks_tune_prune_hdbscan(const double *normalised, int rows, int cols, int min_cluster_size,
+                          int min_samples, int32_t *kept_out, int kept_cap, int32_t *labels_out);
+
 /* Section II-B: fraction of the total variance of the rows of `normalised` carried by each
  * principal component, descending (ratio_out: cols doubles). */
 int ks_tune_pca_variance(const double *normalised, int rows, int cols, double *ratio_out);

@@ -376,3 +376,162 @@ def prune_pca_kmeans(Phat, n, dims, max_iter=100):
     centres, _ = kmeans((X - mean) @ Vd, n, max_iter)
     back = mean + centres @ Vd.T
     return sorted({int(np.argmax(c)) for c in back})
+
+
+# ----------------------------------------------------------------- HDBSCAN pruning (Section III)
+# The last of the clustering methods the paper compares (its Fig. 4): density-based clustering of the
+# normalised performance vectors in which the number of clusters is not a parameter.  The published
+# algorithm (Campello, Moulavi, Sander 2013; McInnes, Healy, Astels 2017), by its steps:
+#   1. core distance of a point = distance to its min_samples-th nearest point, itself included;
+#   2. mutual reachability distance d(a, b) = max(core(a), core(b), |a - b|);
+#   3. minimum spanning tree of the complete graph under d (Prim from point 0; the next vertex is
+#      the one with the smallest key, lowest index on ties; a key changes only if strictly smaller);
+#   4. single-linkage hierarchy: edges in ascending order of weight (order of insertion on ties)
+#      merge components;
+#   5. condensed tree: walking down from the root with lambda = 1 / distance, a split whose two sides
+#      both hold at least min_cluster_size points creates two new clusters; otherwise the points of
+#      a side that is too small fall out of the cluster at that lambda and the other side carries on
+#      as the same cluster;
+#   6. stability of a cluster = sum over the points that leave it (falling out, or in a child
+#      cluster) of lambda_leave - lambda_birth; clusters are selected bottom-up by excess of mass:
+#      a cluster replaces its selected descendants if its stability is at least their sum; the root
+#      is never selected;
+#   7. a point belongs to the nearest selected ancestor of the cluster it fell out of, else is noise.
+# Readings: distances below 1e-12 count as 1e-12 (lambda stays finite); the kept configuration of a
+# cluster is the best one of its centroid, as for k-means; rows labelled noise take no part; if no
+# cluster is selected the centroid of all rows is used.
+HDBSCAN_DMIN = 1e-12
+
+
+def hdbscan_labels(Z, min_cluster_size, min_samples=None):
+    """Cluster labels (0 .. n_clusters-1 in order of first member row; -1 = noise)."""
+    Z = np.asarray(Z, dtype=np.float64)
+    n = Z.shape[0]
+    k = min(int(min_samples if min_samples is not None else min_cluster_size), n)
+    D = np.sqrt(np.maximum(((Z[:, None, :] - Z[None, :, :]) ** 2).sum(axis=2), 0.0)) if n <= 1500 else None
+    if D is None:
+        sq = (Z * Z).sum(axis=1)
+        D = np.sqrt(np.maximum(sq[:, None] + sq[None, :] - 2.0 * Z @ Z.T, 0.0))
+        np.fill_diagonal(D, 0.0)
+    core = np.sort(D, axis=1)[:, k - 1]
+    # Prim
+    in_tree = np.zeros(n, dtype=bool)
+    key = np.full(n, np.inf)
+    parent = np.full(n, -1)
+    key[0] = 0.0
+    edges = []
+    for _ in range(n):
+        cand = np.where(in_tree, np.inf, key)
+        v = int(np.argmin(cand))
+        in_tree[v] = True
+        if parent[v] >= 0:
+            edges.append((float(key[v]), int(parent[v]), v))
+        w = np.maximum(np.maximum(core[v], core), D[v])
+        better = (~in_tree) & (w < key)
+        key[better] = w[better]
+        parent[better] = v
+    order = sorted(range(len(edges)), key=lambda e: (edges[e][0], e))
+    # single linkage: node ids n.. for merges
+    comp = list(range(n))                      # union-find over points -> current dendrogram node
+
+    def find(x):
+        while comp[x] != x:
+            comp[x] = comp[comp[x]]
+            x = comp[x]
+        return x
+    node_of = list(range(n))                   # dendrogram node of each union-find root
+    left, right, dist, size = {}, {}, {}, {i: 1 for i in range(n)}
+    nxt = n
+    for e in order:
+        w, a, b = edges[e]
+        ra, rb = find(a), find(b)
+        na, nb = node_of[ra], node_of[rb]
+        left[nxt], right[nxt], dist[nxt], size[nxt] = na, nb, w, size[na] + size[nb]
+        comp[rb] = ra
+        node_of[ra] = nxt
+        nxt += 1
+    root = nxt - 1
+    if n == 1:
+        return np.full(1, -1)
+
+    def leaves(x):
+        out, stack = [], [x]
+        while stack:
+            y = stack.pop()
+            if y < n:
+                out.append(y)
+            else:
+                stack.extend((right[y], left[y]))
+        return out
+    # condensed tree
+    birth = {0: 0.0}
+    children = {0: []}
+    parent_cluster = {0: -1}
+    fell = {0: []}                              # (point, lambda) leaving cluster c
+    child_mass = {0: []}                        # (size, lambda) of child clusters born from c
+    stack = [(root, 0)]
+    n_clusters = 1
+    while stack:
+        node, c = stack.pop(0)
+        if node < n:
+            fell[c].append((node, np.inf))      # cannot happen for min_cluster_size >= 2; kept for completeness
+            continue
+        lam = 1.0 / max(dist[node], HDBSCAN_DMIN)
+        L, R = left[node], right[node]
+        bigL, bigR = size[L] >= min_cluster_size, size[R] >= min_cluster_size
+        if bigL and bigR:
+            for side in (L, R):
+                cid = n_clusters
+                n_clusters += 1
+                birth[cid], children[cid], parent_cluster[cid], fell[cid], child_mass[cid] = lam, [], c, [], []
+                children[c].append(cid)
+                child_mass[c].append((size[side], lam))
+                stack.append((side, cid))
+        else:
+            for side, big in ((L, bigL), (R, bigR)):
+                if big:
+                    stack.append((side, c))
+                else:
+                    fell[c].extend((p, lam) for p in leaves(side))
+    stability = {c: sum(l - birth[c] for _, l in fell[c]) + sum(s * (l - birth[c]) for s, l in child_mass[c])
+                 for c in birth}
+    selected = {c: False for c in birth}
+    best = dict(stability)
+    for c in sorted(birth, reverse=True):       # children have larger ids than their parents
+        if not children[c]:
+            selected[c] = c != 0
+            continue
+        below = sum(best[ch] for ch in children[c])
+        if c == 0 or stability[c] < below:
+            best[c] = below
+        else:
+            selected[c] = True
+            todo = list(children[c])
+            while todo:
+                d = todo.pop()
+                selected[d] = False
+                todo.extend(children[d])
+    labels = np.full(n, -1)
+    for c in birth:
+        a = c
+        while a != -1 and not selected[a]:
+            a = parent_cluster[a]
+        if a == -1:
+            continue
+        for p, _ in fell[c]:
+            labels[p] = a
+    # renumber in order of first member row
+    remap = {}
+    for i in range(n):
+        if labels[i] >= 0 and labels[i] not in remap:
+            remap[int(labels[i])] = len(remap)
+    return np.array([remap[int(v)] if v >= 0 else -1 for v in labels])
+
+
+def prune_hdbscan(Phat, min_cluster_size, min_samples=None):
+    """Kept configurations: the best configuration of every cluster's centroid."""
+    Phat = np.asarray(Phat, dtype=np.float64)
+    lab = hdbscan_labels(Phat, min_cluster_size, min_samples)
+    if lab.max() < 0:
+        return [int(np.argmax(Phat.mean(axis=0)))], lab
+    return sorted({int(np.argmax(Phat[lab == c].mean(axis=0))) for c in range(lab.max() + 1)}), lab

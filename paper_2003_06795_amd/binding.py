@@ -63,7 +63,7 @@ EXPORTS = [
     "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_bf16_ablation", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_performance", "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
-    "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans",
+    "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans", "ks_tune_prune_hdbscan",
     "ks_tune_pca_variance", "ks_status_string",
 ]
 
@@ -116,6 +116,7 @@ def lib():
     L.ks_tune_selector_score.argtypes = [_p, _i, _i, _p, _p]
     L.ks_tune_prune_top_n.argtypes = [_p, _i, _i, _i, _p]
     L.ks_tune_prune_kmeans.argtypes = [_p, _i, _i, _i, _i, _i, _p]
+    L.ks_tune_prune_hdbscan.argtypes = [_p, _i, _i, _i, _i, _p, _i, _p]
     L.ks_tune_pca_variance.argtypes = [_p, _i, _i, _p]
     L.ks_status_string.argtypes = [_i]
     L.ks_status_string.restype = ctypes.c_char_p
@@ -434,6 +435,19 @@ def tune_prune_kmeans(normalised, n, pca_dims=0, max_iter=100):
     if m < 0:
         raise KsError(m, "ks_tune_prune_kmeans")
     return kept[:m].copy()
+
+
+def tune_prune_hdbscan(normalised, min_cluster_size, min_samples=None):
+    """Returns (kept ids, cluster label of every row; -1 = noise)."""
+    Y, yp = _np(normalised, np.float64)
+    kept = np.zeros(Y.shape[1], dtype=np.int32)
+    labels = np.zeros(Y.shape[0], dtype=np.int32)
+    m = lib().ks_tune_prune_hdbscan(yp, Y.shape[0], Y.shape[1], int(min_cluster_size),
+                                    int(min_samples if min_samples is not None else min_cluster_size),
+                                    kept.ctypes.data_as(_p), len(kept), labels.ctypes.data_as(_p))
+    if m < 0:
+        raise KsError(m, "ks_tune_prune_hdbscan")
+    return kept[:m].copy(), labels
 
 
 def tune_pca_variance(normalised):

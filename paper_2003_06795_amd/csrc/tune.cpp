@@ -14,6 +14,7 @@
 #include <cmath>
 #include <cstring>
 #include <numeric>
+#include <limits>
 #include <vector>
 
 namespace {
@@ -511,6 +512,203 @@ extern "C" int ks_tune_prune_kmeans(const double *normalised, int rows, int cols
             back[(size_t)c * cols + j] = acc;
         }
     return keep_argmax_rows(back, k, cols, kept_out);
+}
+
+// ---------------------------------------------------------------- HDBSCAN (Section III)
+// Density-based clustering of the rows (Campello, Moulavi, Sander 2013; McInnes, Healy, Astels
+// 2017): core distances, mutual reachability, minimum spanning tree, single-linkage hierarchy,
+// condensed tree, excess-of-mass selection.  The number of clusters is a result, not a parameter.
+namespace {
+
+struct CondensedCluster {
+    int parent = -1;
+    double birth = 0.0;
+    double stability = 0.0;
+    std::vector<int> children;
+    std::vector<int> fellPoints;          // rows that left this cluster as single points
+    bool selected = false;
+};
+
+constexpr double kHdbscanDmin = 1e-12;
+
+// labels[i] = cluster of row i (numbered by first member row) or -1; returns the cluster count
+int hdbscan_cluster(const double *Z, int n, int d, int minClusterSize, int minSamples, std::vector<int> &labels) {
+    labels.assign((size_t)n, -1);
+    if (n < 2) return 0;
+    const int k = std::min(std::max(minSamples, 1), n);
+    std::vector<double> D((size_t)n * n);
+    for (int i = 0; i < n; ++i)
+        for (int j = i; j < n; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) {
+                const double t = Z[(size_t)i * d + c] - Z[(size_t)j * d + c];
+                acc += t * t;
+            }
+            D[(size_t)i * n + j] = D[(size_t)j * n + i] = std::sqrt(acc);
+        }
+    std::vector<double> core((size_t)n), row((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        std::copy(D.begin() + (size_t)i * n, D.begin() + (size_t)(i + 1) * n, row.begin());
+        std::nth_element(row.begin(), row.begin() + (k - 1), row.end());
+        core[i] = row[k - 1];
+    }
+    // minimum spanning tree under the mutual reachability distance (Prim from row 0)
+    struct Edge { double w; int a, b, order; };
+    std::vector<Edge> edges;
+    std::vector<char> inTree((size_t)n, 0);
+    std::vector<double> key((size_t)n, std::numeric_limits<double>::infinity());
+    std::vector<int> from((size_t)n, -1);
+    key[0] = 0.0;
+    for (int step = 0; step < n; ++step) {
+        int v = -1;
+        for (int i = 0; i < n; ++i)
+            if (!inTree[i] && (v < 0 || key[i] < key[v])) v = i;
+        inTree[v] = 1;
+        if (from[v] >= 0) edges.push_back(Edge{key[v], from[v], v, (int)edges.size()});
+        for (int i = 0; i < n; ++i) {
+            if (inTree[i]) continue;
+            const double w = std::max(std::max(core[v], core[i]), D[(size_t)v * n + i]);
+            if (w < key[i]) { key[i] = w; from[i] = v; }
+        }
+    }
+    std::sort(edges.begin(), edges.end(), [](const Edge &x, const Edge &y) {
+        return x.w != y.w ? x.w < y.w : x.order < y.order;
+    });
+    // single-linkage hierarchy: nodes 0 .. n-1 are rows, n .. 2n-2 merges
+    const int total = 2 * n - 1;
+    std::vector<int> left((size_t)total, -1), right((size_t)total, -1), size((size_t)total, 1), uf((size_t)n), nodeOf((size_t)n);
+    std::vector<double> dist((size_t)total, 0.0);
+    for (int i = 0; i < n; ++i) { uf[i] = i; nodeOf[i] = i; }
+    auto find = [&](int x) {
+        while (uf[x] != x) { uf[x] = uf[uf[x]]; x = uf[x]; }
+        return x;
+    };
+    int next = n;
+    for (const Edge &e : edges) {
+        const int ra = find(e.a), rb = find(e.b);
+        const int na = nodeOf[ra], nb = nodeOf[rb];
+        left[next] = na; right[next] = nb; dist[next] = e.w; size[next] = size[na] + size[nb];
+        uf[rb] = ra;
+        nodeOf[ra] = next++;
+    }
+    const int root = next - 1;
+    auto collect = [&](int node, std::vector<int> &out) {
+        std::vector<int> stack{node};
+        while (!stack.empty()) {
+            const int y = stack.back();
+            stack.pop_back();
+            if (y < n) out.push_back(y);
+            else { stack.push_back(left[y]); stack.push_back(right[y]); }
+        }
+    };
+    // condensed tree, breadth first from the root; cluster 0 is the root cluster
+    std::vector<CondensedCluster> cl(1);
+    std::vector<double> fellLambdaSum(1, 0.0);       // sum over leaving points / child clusters of lambda_leave
+    std::vector<double> leaveCount(1, 0.0);
+    std::vector<std::pair<int, int>> queue{{root, 0}};
+    for (size_t head = 0; head < queue.size(); ++head) {
+        const int node = queue[head].first, c = queue[head].second;
+        if (node < n) { cl[c].fellPoints.push_back(node); continue; }
+        const double lam = 1.0 / std::max(dist[node], kHdbscanDmin);
+        const int sides[2] = {left[node], right[node]};
+        const bool big[2] = {size[sides[0]] >= minClusterSize, size[sides[1]] >= minClusterSize};
+        if (big[0] && big[1]) {
+            for (int t = 0; t < 2; ++t) {
+                const int id = (int)cl.size();
+                cl.emplace_back();
+                fellLambdaSum.push_back(0.0);
+                leaveCount.push_back(0.0);
+                cl[id].parent = c;
+                cl[id].birth = lam;
+                cl[c].children.push_back(id);
+                fellLambdaSum[c] += lam * size[sides[t]];
+                leaveCount[c] += size[sides[t]];
+                queue.push_back({sides[t], id});
+            }
+        } else {
+            for (int t = 0; t < 2; ++t) {
+                if (big[t]) { queue.push_back({sides[t], c}); continue; }
+                std::vector<int> pts;
+                collect(sides[t], pts);
+                for (int p : pts) cl[c].fellPoints.push_back(p);
+                fellLambdaSum[c] += lam * (double)pts.size();
+                leaveCount[c] += (double)pts.size();
+            }
+        }
+    }
+    const int nc = (int)cl.size();
+    for (int c = 0; c < nc; ++c) cl[c].stability = fellLambdaSum[c] - cl[c].birth * leaveCount[c];
+    // excess of mass, children before parents (children have larger ids)
+    std::vector<double> best((size_t)nc);
+    for (int c = nc - 1; c >= 0; --c) {
+        best[c] = cl[c].stability;
+        if (cl[c].children.empty()) { cl[c].selected = c != 0; continue; }
+        double below = 0.0;
+        for (int ch : cl[c].children) below += best[ch];
+        if (c == 0 || cl[c].stability < below) {
+            best[c] = below;
+        } else {
+            cl[c].selected = true;
+            std::vector<int> todo(cl[c].children);
+            while (!todo.empty()) {
+                const int x = todo.back();
+                todo.pop_back();
+                cl[x].selected = false;
+                for (int ch : cl[x].children) todo.push_back(ch);
+            }
+        }
+    }
+    std::vector<int> raw((size_t)n, -1);
+    for (int c = 0; c < nc; ++c) {
+        int a = c;
+        while (a != -1 && !cl[a].selected) a = cl[a].parent;
+        if (a == -1) continue;
+        for (int p : cl[c].fellPoints) raw[p] = a;
+    }
+    std::vector<int> remap((size_t)nc, -1);
+    int count = 0;
+    for (int i = 0; i < n; ++i)
+        if (raw[i] >= 0) {
+            if (remap[raw[i]] < 0) remap[raw[i]] = count++;
+            labels[i] = remap[raw[i]];
+        }
+    return count;
+}
+
+}  // namespace
+
+extern "C" int ks_tune_prune_hdbscan(const double *normalised, int rows, int cols, int min_cluster_size,
+                                     int min_samples, int32_t *kept_out, int kept_cap, int32_t *labels_out) {
+    if (!normalised || !kept_out || rows <= 0 || cols <= 0 || min_cluster_size < 2 || min_samples < 1 || kept_cap < 1)
+        return KS_ERR_INVALID_ARG;
+    if ((double)rows * rows * sizeof(double) > 4e9) return KS_ERR_UNSUPPORTED;
+    std::vector<int> labels;
+    const int count = hdbscan_cluster(normalised, rows, cols, min_cluster_size, min_samples, labels);
+    if (labels_out)
+        for (int i = 0; i < rows; ++i) labels_out[i] = labels[i];
+    std::vector<char> keep((size_t)cols, 0);
+    auto best_of_mean = [&](int cluster) {
+        std::vector<double> mean((size_t)cols, 0.0);
+        int members = 0;
+        for (int i = 0; i < rows; ++i)
+            if (cluster < 0 || labels[i] == cluster) {
+                ++members;
+                for (int c = 0; c < cols; ++c) mean[c] += normalised[(size_t)i * cols + c];
+            }
+        int arg = 0;
+        for (int c = 1; c < cols; ++c)
+            if (mean[c] / members > mean[arg] / members) arg = c;
+        return arg;
+    };
+    if (count == 0) keep[best_of_mean(-1)] = 1;
+    for (int k = 0; k < count; ++k) keep[best_of_mean(k)] = 1;
+    int n = 0;
+    for (int c = 0; c < cols; ++c)
+        if (keep[c]) {
+            if (n >= kept_cap) return KS_ERR_INVALID_ARG;
+            kept_out[n++] = c;
+        }
+    return n;
 }
 
 extern "C" int ks_tune_pca_variance(const double *normalised, int rows, int cols, double *ratio_out) {

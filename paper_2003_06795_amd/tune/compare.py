@@ -3,10 +3,10 @@ of kept kernels) and Table I (selector vs other classifiers) on a measured timin
 
     python -m paper_2003_06795_amd.tune.compare --dtype f32 --timings <csv> [--out report.json]
 
-Pruning (top-N by wins, k-means, PCA + k-means, decision tree), the PCA spectrum, the selector
+Pruning (top-N by wins, k-means, PCA + k-means, HDBSCAN, decision tree), the PCA spectrum, the selector
 tree and every score are computed by the library's host tuner (ks_tune_*).  The other classifiers
 of Table I are comparison systems, not part of the library: they are run with scikit-learn when it
-is importable (as in the paper) and skipped otherwise.  HDBSCAN is not reproduced.
+is importable (as in the paper) and skipped otherwise.
 """
 import argparse
 import json
@@ -46,26 +46,16 @@ def other_classifiers(Xtr, ytr, Xte):
 
 
 def hdbscan_pruning(Ph_tr, Ph_te):
-    """Section III's density-clustering pruner, as a report only: like the paper it uses a library
-    (scikit-learn's HDBSCAN, when importable).  The number of clusters is not a parameter, so the
-    minimum cluster size is swept; a cluster's representative is its mean vector, noise rows are
-    left out, and the kept set is the best configuration of each representative."""
-    try:
-        from sklearn.cluster import HDBSCAN
-    except ImportError:
-        return []
+    """HDBSCAN has no "number of clusters" parameter: sweep its minimum cluster size (the library's
+    ks_tune_prune_hdbscan, minimum samples = minimum cluster size) and report what each setting keeps."""
     out, seen = [], set()
     for mcs in (2, 3, 4, 5, 6, 8, 10, 15, 20, 30, 40):
-        labels = HDBSCAN(min_cluster_size=mcs).fit_predict(Ph_tr)
-        ids = sorted(set(int(l) for l in labels if l >= 0))
-        if not ids:
-            continue
-        kept = np.unique([int(np.argmax(Ph_tr[labels == l].mean(axis=0))) for l in ids]).astype(np.int32)
+        kept, labels = ks.tune_prune_hdbscan(Ph_tr, mcs)
         key = tuple(kept.tolist())
         if key in seen:
             continue
         seen.add(key)
-        out.append(dict(min_cluster_size=mcs, clusters=len(ids), noise_rows=int((labels < 0).sum()),
+        out.append(dict(min_cluster_size=mcs, clusters=int(labels.max()) + 1, noise_rows=int((labels < 0).sum()),
                         kept=kept.tolist(), achievable=ks.tune_achievable(Ph_te, kept)))
     return sorted(out, key=lambda r: len(r["kept"]))
 

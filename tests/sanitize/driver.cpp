@@ -147,6 +147,12 @@ static void tuner_cases() {
                 REQUIRE(ks_tune_prune_kmeans(Ph.data(), rows, cols, leaves, pd, 50, k2.data()) >= 1);
             }
         }
+        if (rows >= 5) {
+            std::vector<int32_t> kh((size_t)cols), lab((size_t)rows);
+            for (int mcs : {2, 5, 40})
+                REQUIRE(ks_tune_prune_hdbscan(Ph.data(), rows, cols, mcs, mcs < 5 ? 1 : mcs, kh.data(), cols, lab.data()) >= 1);
+            REQUIRE(ks_tune_prune_hdbscan(Ph.data(), rows, cols, 1, 1, kh.data(), cols, nullptr) < 0);
+        }
         std::vector<double> ratio((size_t)cols);
         // a table without variance (one row, or one column of ones) is refused, anything else is not
         REQUIRE(ks_tune_pca_variance(Ph.data(), rows, cols, ratio.data()) == (rows > 1 && cols > 1 ? KS_OK : KS_ERR_INVALID_ARG));
