@@ -65,7 +65,7 @@ def kernel_symbol(ks, dt, plan, tA, tB):
             b(plan["tiles_per_workgroup"] > 1))
     f = 16 if ki["core_name"] == "mfma16" else 32
     if plan["path"] == 2:
-        return "gemm_bf16_pp_kernel<%d, %s, %s, %s, false>" % (f, b(split), b(akc), b(bkc))
+        return "gemm_bf16_pp_kernel<%d, %s, %s, %s, false, 0>" % (f, b(split), b(akc), b(bkc))
     if plan["path"] == 1:
         stages = ki["lds_bytes"] // (ki["bk"] * (ki["bm"] + ki["bn"]) * 2)
         return "gemm_bf16_dma_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %s, false>" % (
@@ -185,7 +185,7 @@ def stored_traffic(workload, symbol):
     if not os.path.exists(path):
         return None
     for k in json.load(open(path)).get("kernels", []):
-        if k["kernel"] == symbol:
+        if k["kernel"] == symbol or k["kernel"].startswith(symbol.rstrip(">")):
             return dict(fetch_bytes=k["fetch_bytes"], write_bytes=k["write_bytes"],
                         total_bytes=k["fetch_bytes"] + k["write_bytes"], algorithmic_bytes=k.get("algorithmic_bytes"))
     return None

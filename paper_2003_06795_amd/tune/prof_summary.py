@@ -36,7 +36,7 @@ def main(argv=None):
     cum, shown = 0.0, 0
     for r in rows:
         name = short(r["Name"])
-        is_roof = roof is not None and name.startswith(roof["kernel"])
+        is_roof = roof is not None and name.startswith(roof["kernel"].rstrip(">"))
         if (cum < a.share * total and shown < a.max_rows) or is_roof:
             print("%-100s %8d %12.3f %10.3f %6.2f%s" % (name[:100], int(r["Calls"]), float(r["TotalDurationNs"]) / 1e6,
                                                        float(r["AverageNs"]) / 1e3,
