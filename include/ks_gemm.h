@@ -32,7 +32,7 @@
  *     one exception: the registered workspace is a single buffer, so two GEMMs
  *     that both run a split-K member must not be in flight together (same
  *     stream, or ordered by the caller).  ks_set_workspace, ks_set_fast_path,
- *     ks_set_tiles_per_workgroup,
+ *     ks_set_tiles_per_workgroup, ks_set_balanced_groups,
  *     ks_set_selector and ks_time_gemm are not thread-safe.  The library acts
  *     on the calling thread's current HIP device and never changes it.
  */
@@ -88,6 +88,14 @@ typedef struct {
     int32_t available;   /* 1: compiled into this library; 0: pruned away (a library built with only the
                             kept set of the deployed trees, Section III, holds the kept members and the
                             four bring-up tiles; forcing an absent member returns KS_ERR_UNSUPPORTED) */
+    int32_t balanced_per_cu; /* > 0: the member has a balanced persistent form (the launch shape, the
+                            run-time axis of the Section II kernel, is then a fixed 256 * balanced_per_cu
+                            work-groups that each compute the same number of K-steps: whole tiles
+                            first, then an equal share of the tiles left over, whose parts a second
+                            kernel adds in K order).  Taken per call where it pays: tiles that do
+                            not divide evenly over those work-groups, fewer than four rounds of them,
+                            K >= 1024, and a registered workspace of ks_workspace_bytes_needed()
+                            bytes; the plain member of the same tiles runs otherwise.  0: no such form */
 } ks_kernel_info_t;
 
 /* Node of a deployed decision tree (Section IV: nested integer comparisons).
@@ -213,6 +221,8 @@ typedef struct {
     int32_t grid_3d;              /* launched (tilesN, tilesM, batch * split_k) instead of one-dimensional */
     int32_t tiles_per_workgroup;  /* > 1: the multi-tile form of the large fp32 members */
     int64_t workgroups;
+    int32_t balanced_groups;      /* > 0: the balanced persistent form runs, with this many work-groups */
+    int32_t divided_tiles;        /* left-over tiles of that form, handed to its second kernel (0: none launched) */
 } ks_launch_plan_t;
 int ks_gemm_plan(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
                  float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
@@ -271,6 +281,15 @@ int ks_set_fast_path(int enabled);
  * and tuning.  Results do not depend on it (every tile is computed the same way whoever walks it).
  * Not thread-safe. */
 int ks_set_tiles_per_workgroup(int n);
+
+/* The members with a balanced persistent form (ks_kernel_info_t::balanced_per_cu > 0) launch
+ * 256 * balanced_per_cu work-groups (the launch shape is the run-time axis of the Section II
+ * kernel).  1 <= per_cu <= 8 forces another count per compute unit for testing and tuning, and
+ * makes those members take the form on every call whose scratch is there (or that divides no
+ * tile); 0 restores the members' own count and the per-call choice.  ks_workspace_bytes_needed
+ * follows the forced count.  Results stay within the stated bound but the summation order of
+ * divided tiles changes with the count.  Not thread-safe. */
+int ks_set_balanced_groups(int per_cu);
 
 /* Measurement aid: copies `bytes` (a multiple of 16; both device pointers 16-byte aligned) with a
  * plain one-read-one-write kernel (ks::copy_kernel).  Hardware traffic counters collected over a

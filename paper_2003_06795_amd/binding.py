@@ -24,7 +24,7 @@ FEATURE_NAMES = ["M", "N", "K", "batch", "transA", "transB", "M*N", "M*N*K", "mi
 class KernelInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("id", "dtype", "core", "bm", "bn", "bk", "wm", "wn", "tm", "tn", "threads",
-                 "split_k", "lds_bytes", "k_waves", "band_rows", "available")]
+                 "split_k", "lds_bytes", "k_waves", "band_rows", "available", "balanced_per_cu")]
 
     def as_dict(self):
         d = {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -35,7 +35,7 @@ class KernelInfo(ctypes.Structure):
 class LaunchPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("kernel_id", "split_k", "path", "vector_loads", "grid_3d", "tiles_per_workgroup")] + \
-               [("workgroups", ctypes.c_int64)]
+               [("workgroups", ctypes.c_int64), ("balanced_groups", ctypes.c_int32), ("divided_tiles", ctypes.c_int32)]
 
 
 class TreeNode(ctypes.Structure):
@@ -61,7 +61,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
     "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_bf16_ablation", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
-    "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_workspace", "ks_workspace_bytes_needed",
+    "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_balanced_groups", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_performance", "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans", "ks_tune_prune_hdbscan",
     "ks_tune_pca_variance", "ks_status_string",
@@ -104,6 +104,7 @@ def lib():
     L.ks_bf16_ablation.argtypes = [_i, _p, _p, _p, _i64, _i64, _i64, _p, _i, _p]
     L.ks_set_fast_path.argtypes = [_i]
     L.ks_set_tiles_per_workgroup.argtypes = [_i]
+    L.ks_set_balanced_groups.argtypes = [_i]
     L.ks_set_workspace.argtypes = [_p, ctypes.c_size_t]
     L.ks_workspace_bytes_needed.argtypes = [_i, _i, _i64, _i64, _i64]
     L.ks_workspace_bytes_needed.restype = ctypes.c_size_t
@@ -326,6 +327,11 @@ def set_fast_path(enabled):
 def set_tiles_per_workgroup(n):
     """0: chosen per call; 1..64: forced (large-tile fp32 MFMA members, 1-D launches without split-K)."""
     _check(lib().ks_set_tiles_per_workgroup(int(n)), "ks_set_tiles_per_workgroup")
+
+
+def set_balanced_groups(per_cu):
+    """0: each member's own count; 1..8: forced work-groups per compute unit of the balanced persistent form."""
+    _check(lib().ks_set_balanced_groups(int(per_cu)), "ks_set_balanced_groups")
 
 
 def set_workspace(buf, nbytes=None):

@@ -45,9 +45,13 @@ const InstanceDesc kF32[kNumF32] = {
                                                  ((KW) > 1 ? (KW) * BM * BN * 4 : 0),                     \
      KS_CORE_OF_##CORE == KS_CORE_KSLICE ? P1 : (KW)},
 #define KS_F32_INSTANCE(id, CORE, BM, BN, BK, P1, P2, SPLITK) KS_F32_INSTANCE_KW(id, CORE, BM, BN, BK, P1, P2, SPLITK, 1)
+#define KS_F32_INSTANCE_SK(id, CORE, BM, BN, BK, P1, P2, PERCU)                                          \
+    {id, KS_CORE_OF_##CORE, BM, BN, BK, P1, P2, threads_of(KS_CORE_OF_##CORE, BM, BN, P1, P2), 1,         \
+     2 * BK * ((BM + (BK < 16 ? 64 / BK : 4)) + (BN + (BK < 16 ? 64 / BK : 4))) * 4, 1, 8, PERCU},
 #include "instances.def"
 #undef KS_F32_INSTANCE
 #undef KS_F32_INSTANCE_KW
+#undef KS_F32_INSTANCE_SK
 };
 
 const InstanceDesc kBf16[kNumBf16] = {
@@ -91,6 +95,7 @@ void init_tables() {
 
 int g_forceGeneric = 0;
 int g_tilesPerWG = 0;        // 0: chosen per call (multi_tiles); n >= 1: forced
+int g_skPerCU = 0;           // 0: the member's own count of work-groups per compute unit; n >= 1: forced
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
@@ -147,6 +152,13 @@ int multi_tiles(const InstanceDesc *d, int64_t tiles, int64_t K) {
     const int64_t rounds = tiles / slots;
     if (K > 2 * d->bk || rounds < 32) return 1;
     return (int)(rounds / 8 < 8 ? rounds / 8 : 8);
+}
+
+// Balanced persistent form: work-groups of the launch, and the scratch its divided tiles need (two
+// raw accumulator tiles per work-group: the head and the tail of its share of the left-over tiles).
+int64_t sk_groups(const InstanceDesc *d) { return 256LL * (g_skPerCU > 0 ? g_skPerCU : d->sk); }
+size_t sk_workspace_bytes(const InstanceDesc *d) {
+    return (size_t)sk_groups(d) * 2 * (size_t)d->bm * (size_t)d->bn * sizeof(float);
 }
 
 const InstanceDesc *desc_of(int dtype, int id) {
@@ -348,7 +360,30 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
                    : 0;
     p.tilesPerWG = 1;
     p.bandRows = d->band;
-    if (dtype == KS_F32 && !p.grid3d && p.splitK == 1 && f32_multi_tile(d->core, d->bm, d->bn, d->p1, d->p2, d->kw)) {
+    p.skGroups = 0; p.skRounds = 0; p.skTailTiles = 0;
+    if (d->sk > 0) {
+        // Balanced persistent form where it pays (measured against the plain member of the same
+        // tiles on the tuning tables): tiles that do not divide evenly over the work-groups, fewer
+        // than four rounds of them (with more, the uneven last round matters less than what the
+        // hardware's own dispatch gains by handing a tile to whichever unit is free), and at
+        // least 1024 of K per tile and one K-step per share (below that the raw accumulator tiles
+        // of the divided tiles and the second kernel cost more than the balance gains).  A forced work-group count
+        // (ks_set_balanced_groups) takes the form whenever it can run.  Its scratch must be there
+        // unless no tile is divided; otherwise the plain member runs.
+        const int64_t groups = sk_groups(d);
+        const int64_t tail = grid64 % groups;
+        const bool fits = tail == 0 || (wsp.ptr && wsp.bytes >= sk_workspace_bytes(d) && aligned(wsp.ptr, 16));
+        const bool pays = g_skPerCU > 0 || (tail != 0 && grid64 < 4 * groups && K >= 1024 && tail * kTiles >= groups);
+        if (fits && pays && tail * kTiles < (1LL << 50)) {
+            p.skGroups = (int)groups;
+            p.skRounds = (int)(grid64 / groups);
+            p.skTailTiles = (int)tail;
+            p.ws = static_cast<float *>(wsp.ptr);
+            p.grid3d = 0;
+            grid64 = groups;
+        }
+    }
+    if (dtype == KS_F32 && !p.grid3d && p.splitK == 1 && p.skGroups == 0 && f32_multi_tile(d->core, d->bm, d->bn, d->p1, d->p2, d->kw)) {
         p.tilesPerWG = g_tilesPerWG > 0 ? g_tilesPerWG : multi_tiles(d, grid64, K);
         grid64 = (grid64 + p.tilesPerWG - 1) / p.tilesPerWG;
     }
@@ -380,6 +415,8 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
         planOnly->grid_3d = p.grid3d;
         planOnly->tiles_per_workgroup = p.tilesPerWG;
         planOnly->workgroups = grid64;
+        planOnly->balanced_groups = p.skGroups;
+        planOnly->divided_tiles = p.skTailTiles;
         planOnly->path = !dma ? 0
                          : bf16_two_groups(d->core == KS_CORE_MFMA32 ? 32 : 16, d->bm, d->bn, d->bk, d->p1, d->p2,
                                            d->ldsBytes / (d->bk * (d->bm + d->bn) * 2))
@@ -452,6 +489,7 @@ extern "C" int ks_kernel_info(int dtype, int kernel_id, ks_kernel_info_t *out) {
     out->split_k = d->splitK;
     out->lds_bytes = d->ldsBytes;
     out->band_rows = d->band;
+    out->balanced_per_cu = d->sk;
     std::call_once(g_once, init_tables);
     out->available = (dtype == KS_F32 ? g_f32[kernel_id] : g_bf16[kernel_id]) != nullptr ? 1 : 0;
     return KS_OK;
@@ -480,6 +518,12 @@ extern "C" int ks_set_tiles_per_workgroup(int n) {
     return KS_OK;
 }
 
+extern "C" int ks_set_balanced_groups(int per_cu) {
+    if (per_cu < 0 || per_cu > 8) return KS_ERR_INVALID_ARG;
+    g_skPerCU = per_cu;
+    return KS_OK;
+}
+
 extern "C" int ks_set_workspace(void *device_ptr, size_t bytes) {
     if (device_ptr == nullptr || bytes == 0) {
         g_ws = nullptr;
@@ -495,7 +539,9 @@ extern "C" int ks_set_workspace(void *device_ptr, size_t bytes) {
 extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N,
                                             int64_t batch) {
     const InstanceDesc *d = desc_of(dtype, kernel_id);
-    if (!d || d->splitK == 1 || M <= 0 || N <= 0 || batch <= 0) return 0;
+    if (!d || M <= 0 || N <= 0 || batch <= 0) return 0;
+    if (d->sk > 0) return sk_workspace_bytes(d);
+    if (d->splitK == 1) return 0;
     int64_t s = d->splitK;
     if (s == 0) {
         s = auto_split_max(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch, dtype == KS_F32);

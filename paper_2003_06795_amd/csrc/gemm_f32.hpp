@@ -40,6 +40,12 @@ namespace ks {
 #ifndef KS_F32_MIN_WAVES
 #define KS_F32_MIN_WAVES(multi, core, bm, bn, bk, p1, p2) ((multi) && ((bm) / (p1)) * ((bn) / (p2)) <= 4 ? 3 : 0)
 #endif
+// The balanced persistent form counts on a fixed number of resident work-groups per compute unit:
+// two of eight waves (four waves per SIMD, 128 registers) or three of four waves (three per SIMD),
+// which is what the plain forms of those members reach.
+#ifndef KS_F32_SK_MIN_WAVES
+#define KS_F32_SK_MIN_WAVES(bm, bn, p1, p2) (((bm) / (p1)) * ((bn) / (p2)) >= 8 ? 4 : 3)
+#endif
 
 enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3, CORE_KSLICE = 4 };
 
@@ -135,11 +141,23 @@ struct TileLoader {
 // MULTI (members for which f32_multi_tile holds, never split-K): the work-group walks
 // GemmParams::tilesPerWG consecutive logical tiles.  The single-tile form of the same member is a
 // separate instantiation: the flattened loop costs it about 6 % on ordinary shapes.
+//
+// SK (32x32 MFMA members, single K group, never split-K): the balanced persistent form.  The launch
+// holds a fixed number of work-groups (a few per compute unit, all resident at once).  Each first
+// computes GemmParams::skRounds whole tiles, then an equal share of the K-steps of the tiles that
+// are left over when the tile count is not a multiple of the work-group count: those tiles are
+// flattened into one sequence of (tile, K-step) units and cut into contiguous shares, so every
+// compute unit gets the same number of K-steps however unevenly the tiles divide.  A share that
+// covers a whole tile is written to C as usual; a share that covers part of a tile goes to the
+// workspace as a raw accumulator tile (at most two per work-group: the head and the tail of its
+// share), and gemm_f32_sk_fixup_kernel adds the parts of every divided tile in K order and applies
+// the epilogue.  No work-group waits for another, so there is nothing to deadlock on.
 template <int CORE, int BM, int BN, int BK, int P1, int P2, bool SPLIT, bool AKC, bool BKC, bool VEC,
-          int KW = 1, bool MULTI = false>
-__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), KS_F32_MIN_WAVES(MULTI, CORE, BM, BN, BK, P1, P2)) void gemm_f32_kernel(
+          int KW = 1, bool MULTI = false, bool SK = false>
+__global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), (SK ? KS_F32_SK_MIN_WAVES(BM, BN, P1, P2) : KS_F32_MIN_WAVES(MULTI, CORE, BM, BN, BK, P1, P2))) void gemm_f32_kernel(
     const GemmParams p) {
     static_assert(!MULTI || (f32_multi_tile(CORE, BM, BN, P1, P2, KW) && !SPLIT), "multi-tile form");
+    static_assert(!SK || (CORE == CORE_MFMA32 && KW == 1 && !SPLIT && !MULTI), "balanced persistent form");
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
     constexpr int NT = Shape::threads;                        // threads of one group
     static_assert(KW == 1 || CORE != CORE_FMA, "K groups need an MFMA core");
@@ -333,6 +351,103 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), KS_
         return;
     }
 
+    if constexpr (SK) {
+        // Everything that describes the share is the same for all lanes; the integer divisions run
+        // on the vector unit, so their results are moved to scalar registers explicitly.
+        auto uni = [](long long v) -> long long {
+            const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)v);
+            const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)v >> 32));
+            return (long long)(((unsigned long long)hi << 32) | lo);
+        };
+        const unsigned lw = (unsigned)__builtin_amdgcn_readfirstlane((int)logical_of_block());
+        const long long groups = (long long)gridDim.x;
+        const int nkT = (p.K + BK - 1) / BK;
+        const long long units = (long long)p.skTailTiles * nkT;
+        const long long ub = uni(sk_share_begin(lw, units, groups)), ue = uni(sk_share_begin(lw + 1, units, groups));
+        const long long t0 = uni(ub / nkT);                  // first left-over tile of the share
+        const int r0 = (int)(ub - t0 * nkT);                  // and the K-step it starts at
+        const int tailSegs = ue > ub ? (int)(uni((ue - 1) / nkT) - t0) + 1 : 0;
+        const int nSeg = p.skRounds + tailSegs;
+        for (int sg = 0; sg < nSeg; ++sg) {
+            unsigned logical;
+            int ks0 = 0, ks1 = nkT;
+            if (sg < p.skRounds) {
+                logical = (unsigned)sg * (unsigned)groups + lw;
+            } else {
+                const long long t = t0 + (sg - p.skRounds);
+                logical = (unsigned)p.skRounds * (unsigned)groups + (unsigned)t;
+                ks0 = sg == p.skRounds ? r0 : 0;
+                ks1 = (int)min((long long)nkT, ue - t * nkT);
+            }
+            TileCoord tcS = tile_of_logical(p, logical);
+            tcS.batch = __builtin_amdgcn_readfirstlane(tcS.batch);
+            tcS.tm = __builtin_amdgcn_readfirstlane(tcS.tm);
+            tcS.tn = __builtin_amdgcn_readfirstlane(tcS.tn);
+            tcS.split = 0;
+            const int rowS = tcS.tm * BM, colS = tcS.tn * BN;
+            const float *AbS = static_cast<const float *>(p.A) + (long long)tcS.batch * p.strideA;
+            const float *BbS = static_cast<const float *>(p.B) + (long long)tcS.batch * p.strideB;
+            const int kB = ks0 * BK, kE = min(p.K, ks1 * BK), nkS = ks1 - ks0;
+            // every staging set is (re)defined here, so none stays alive across the epilogue of the
+            // previous tile; steps past the end of the range are zero tiles that touch no memory
+#pragma unroll
+            for (int d = 0; d < PF; ++d) {
+                la[d].load(AbS, p.lda, rowS, p.M, kB + d * BK, kE, tid);
+                lb[d].load(BbS, p.ldb, colS, p.N, kB + d * BK, kE, tid);
+            }
+            la[0].store(As[0], tid);
+            lb[0].store(Bs[0], tid);
+            __syncthreads();
+            for (int kt0 = 0; kt0 < nkS; kt0 += PF) {
+#pragma unroll
+                for (int u = 0; u < PF; ++u) {
+                    const int kt = kt0 + u;
+                    if (kt >= nkS) break;
+                    const int cur = kt & 1;
+                    if (kt + PF < nkS) {
+                        const int k0 = kB + (kt + PF) * BK;
+                        la[u].load(AbS, p.lda, rowS, p.M, k0, kE, tid);
+                        lb[u].load(BbS, p.ldb, colS, p.N, k0, kE, tid);
+                    }
+                    compute_step(As[cur], Bs[cur]);
+                    if (kt + 1 < nkS) {
+                        la[(u + 1) % PF].store(As[cur ^ 1], tid);
+                        lb[(u + 1) % PF].store(Bs[cur ^ 1], tid);
+                    }
+                    __syncthreads();
+                }
+            }
+            // the lane's output offsets are recomputed for every tile (the compiler would otherwise
+            // keep them in registers across the K loop, which has none to spare)
+            int laneE = lane;
+            asm volatile("" : "+v"(laneE));
+            if (ks0 == 0 && ks1 == nkT) {
+                float *CbS = p.C + (long long)tcS.batch * p.strideC;
+                write_tile_mfma32<false, FM, FN>(p, tcS, CbS, rowS + subM, colS + subN, laneE, acc32);
+            } else {
+                // raw accumulators, in register order: float4 unit (wave, i, j, chunk) of lane l
+                floatx4 *part = reinterpret_cast<floatx4 *>(p.ws) +
+                                ((long long)lw * 2 + (sg == p.skRounds ? 0 : 1)) * (BM * BN / 4);
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            part[(((wave * FM + i) * FN + j) * 4 + c) * 64 + laneE] =
+                                floatx4{acc32[i][j][4 * c], acc32[i][j][4 * c + 1], acc32[i][j][4 * c + 2],
+                                        acc32[i][j][4 * c + 3]};
+            }
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+        }
+        return;
+    }
+
 #pragma unroll
     for (int d = 0; d < PF; ++d)
         if (d < nk) {
@@ -423,6 +538,82 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), KS_
     } else {
         write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + subM, col0 + subN, lane, acc32);
     }
+}
+
+// Second kernel of the balanced persistent form: one single-wave work-group per left-over tile and
+// wave tile (blockIdx.x = tile, blockIdx.y = wave of the first kernel's work-group).  A tile that
+// one share covered whole was written by the first kernel and is skipped; for a divided tile the
+// raw accumulator tiles of its shares are added in K order (ascending work-group, a fixed order:
+// results are reproducible) and stored through the usual epilogue.  Lanes map to accumulator
+// elements exactly as in gemm_f32_kernel.
+template <int BM, int BN, int BK, int P1, int P2>
+__global__ __launch_bounds__(64) void gemm_f32_sk_fixup_kernel(const GemmParams p) {
+    constexpr int FM = P1 / 32, FN = P2 / 32;
+    const long long groups = p.skGroups;
+    const int nkT = (p.K + BK - 1) / BK;
+    const long long units = (long long)p.skTailTiles * nkT;
+    const long long t = blockIdx.x, u0 = t * nkT, u1 = u0 + nkT;
+    // first work-group whose share reaches into this tile
+    long long w = (u0 * groups) / units;
+    while (w > 0 && sk_share_begin(w, units, groups) > u0) --w;
+    while (sk_share_begin(w + 1, units, groups) <= u0) ++w;
+    if (sk_share_begin(w, units, groups) <= u0 && sk_share_begin(w + 1, units, groups) >= u1) return;
+
+    const int lane = (int)threadIdx.x, wave = (int)blockIdx.y;
+    floatx16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    // the parts are fetched four shares at a time (all loads of a batch are independent) and
+    // added in share order
+    constexpr int PB = 4;
+    bool more = true;
+    do {
+        const floatx4 *part[PB];
+        bool have[PB];
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            have[q] = false;
+            part[q] = nullptr;
+            while (more) {
+                if (w >= groups) { more = false; break; }
+                const long long b = sk_share_begin(w, units, groups), e = sk_share_begin(w + 1, units, groups);
+                if (b >= u1) { more = false; break; }
+                const long long cur = w++;
+                if (e <= b) continue;                        // an empty share wrote nothing
+                part[q] = reinterpret_cast<const floatx4 *>(p.ws) + (cur * 2 + (b / nkT == t ? 0 : 1)) * (BM * BN / 4) +
+                          (long long)wave * (FM * FN * 4 * 64) + lane;
+                have[q] = true;
+                break;
+            }
+        }
+        floatx4 v[PB][FM * FN * 4];
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            if (have[q]) {
+#pragma unroll
+                for (int f = 0; f < FM * FN * 4; ++f) v[q][f] = part[q][f * 64];
+            }
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            if (have[q]) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) acc[i][j][4 * c + x] += v[q][(i * FN + j) * 4 + c][x];
+            }
+    } while (more);
+    const TileCoord tc = tile_of_logical(p, (unsigned)p.skRounds * (unsigned)groups + (unsigned)t);
+    float *Cb = p.C + (long long)tc.batch * p.strideC;
+    const int subM = (wave / (BN / P2)) * P1, subN = (wave % (BN / P2)) * P2;
+    write_tile_mfma32<false, FM, FN>(p, tc, Cb, tc.tm * BM + subM, tc.tn * BN + subN, lane, acc);
 }
 
 }  // namespace ks

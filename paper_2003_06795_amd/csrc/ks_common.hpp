@@ -29,7 +29,17 @@ struct GemmParams {
                                      //    then 0 and the batch stride, in elements, is strideC16
     long long strideC16;
     float alpha, beta;
+    // balanced persistent form (fp32 members that have one; 0 everywhere else): the launch holds
+    // skGroups work-groups; each computes skRounds whole tiles (logical tiles round * skGroups + its
+    // own logical id) and then an equal share of the K-steps of the skTailTiles tiles that are left
+    int skGroups, skRounds, skTailTiles;
 };
+
+// K-steps [first, last) of the left-over tiles (flattened as tile * steps-per-tile + step) that
+// work-group `w` of `groups` computes in the balanced persistent form; shares differ by at most one
+__host__ __device__ inline long long sk_share_begin(long long w, long long units, long long groups) {
+    return (w * units) / groups;
+}
 
 // bf16 <-> fp32 for an output kept in bf16: widening is exact, narrowing rounds to nearest even
 // (NaN stays NaN)

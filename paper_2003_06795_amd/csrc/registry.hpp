@@ -10,6 +10,7 @@ typedef void (*LaunchFn)(const GemmParams &p, int grid, int variant, hipStream_t
 struct InstanceDesc {
     int id, core, bm, bn, bk, p1, p2, threads, splitK, ldsBytes, kw;
     int band = 8;        // tile rows per band of the one-dimensional tile order
+    int sk = 0;          // > 0: has a balanced persistent form of 256 * sk work-groups
 };
 
 // Pruned library (paper Sections I and II-B: every instantiation costs binary size and build time,

@@ -70,6 +70,10 @@ def rows_of(config, limit=None, seed=0):
         # large fp32 shapes (all three dimensions 2048 .. 8192): training only
         for i, (s, tA, tB, M, N, K, b) in enumerate(wl.large_fp32_rows()):
             out.append((i, "f32", tA, tB, M, N, K, b, 1.0, 0.0))
+    elif config == 13:
+        # medium-to-large fp32 shapes (dimensions 1024 .. 8192): training only
+        for i, (s, tA, tB, M, N, K, b) in enumerate(wl.medium_large_fp32_rows()):
+            out.append((i, "f32", tA, tB, M, N, K, b, 1.0, 0.0))
     elif config == 11:
         # more batched small shapes (other dimensions and batch sizes): training only
         for i, (M, N, K, b) in enumerate(wl.config4_extra_rows()):

@@ -82,7 +82,7 @@ def split_rows(rows):
     return tr, te
 
 
-LAYOUTS_PER_SHAPE = {2: 4, 7: 4, 12: 4, 6: 2, 8: 2, 5: 2}      # rows of one shape are consecutive in these configs
+LAYOUTS_PER_SHAPE = {2: 4, 7: 4, 12: 4, 13: 4, 6: 2, 8: 2, 5: 2}      # rows of one shape are consecutive in these configs
 
 
 def validation_split(rows, tr, fraction=0.2, seed=0x5a17):

@@ -1,0 +1,179 @@
+"""GPU parity of the balanced persistent form (fp32 members with balanced_per_cu > 0): a fixed
+number of work-groups, whole tiles first, then equal shares of the K-steps of the left-over tiles,
+whose parts a second kernel adds.  Compared with the CPU oracle through the C ABI."""
+import itertools
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from helpers import tolerance, c_padding_mask
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = list(itertools.product((0, 1), (0, 1)))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    import gpu_util
+    return gpu_util
+
+
+@pytest.fixture()
+def ks():
+    import paper_2003_06795_amd.binding as ks
+    yield ks
+    ks.set_balanced_groups(0)
+
+
+def balanced_ids(ks):
+    return [i for i in range(ks.num_kernels(ks.F32)) if ks.kernel_info(ks.F32, i)["balanced_per_cu"] > 0]
+
+
+def plain_twin(ks, kid):
+    """The member with the same tiles, K-step and no split: what a balanced member runs as when it
+    has no scratch."""
+    a = ks.kernel_info(ks.F32, kid)
+    for i in range(ks.num_kernels(ks.F32)):
+        b = ks.kernel_info(ks.F32, i)
+        if i != kid and b["balanced_per_cu"] == 0 and b["split_k"] == 1 and b["k_waves"] == 1 and \
+                all(a[f] == b[f] for f in ("core", "bm", "bn", "bk", "wm", "wn")):
+            return i
+    return None
+
+
+def check(p, got, ref, what):
+    live = ~c_padding_mask(p)
+    err = float(np.max(np.abs(got[live].astype(np.float64) - ref[live].astype(np.float64))))
+    assert np.all(np.isfinite(got[live])), what
+    assert err <= tolerance(p), "%s: max|diff| %.3e > tol %.3e" % (what, err, tolerance(p))
+    mask = c_padding_mask(p)
+    assert np.array_equal(got[mask], p.C0[mask], equal_nan=True), what + ": wrote outside C's logical entries"
+
+
+def plan_of(ks, gpu, dp, kid):
+    p = dp.p
+    return ks.gemm_plan(ks.F32, kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb, p.beta,
+                        dp.C0, p.ldc, p.batch, p.strideA, p.strideB, p.strideC)
+
+
+def test_family_has_balanced_members(ks):
+    ids = balanced_ids(ks)
+    assert ids, "no member with a balanced persistent form"
+    for kid in ids:
+        ki = ks.kernel_info(ks.F32, kid)
+        assert ki["core_name"] == "mfma32" and ki["split_k"] == 1 and ki["k_waves"] == 1
+        assert plain_twin(ks, kid) is not None
+        need = ks.workspace_bytes_needed(ks.F32, kid, 1000, 1000, 1)
+        assert need == 256 * ki["balanced_per_cu"] * 2 * ki["bm"] * ki["bn"] * 4
+
+
+# (tiles of 64 / 128 rows and columns: the counts below give, with 256 work-groups, one whole round
+# plus divided left-over tiles; with 512 or 768 work-groups only divided tiles)
+SHAPES = [
+    # M, N, K, batch, pad, batch_pad, per_cu
+    (1283, 964, 300, 1, (0, 0, 0), (0, 0, 0), 1),      # ragged edges, scalar loads (K = 300 is a multiple of 4 but M is odd)
+    (1288, 968, 296, 1, (4, 8, 4), (0, 0, 0), 1),      # float4 loads, padded leading dimensions
+    (520, 392, 1064, 3, (0, 0, 0), (8, 16, 24), 0),    # batched, member's own work-group count
+    (392, 264, 4104, 1, (0, 0, 0), (0, 0, 0), 0),      # a dozen tiles, long K: every tile cut into many shares
+    (2184, 2056, 72, 1, (0, 0, 0), (0, 0, 0), 1),      # several whole rounds, short K (shares of one or two steps)
+]
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+@pytest.mark.parametrize("shape", SHAPES)
+def test_balanced_form_within_tolerance(gpu, ks, shape, tA, tB):
+    M, N, K, batch, pad, bpad, per_cu = shape
+    p = wl.make_problem("f32", tA, tB, M, N, K, batch=batch, alpha=1.25, beta=-0.5, seed=31,
+                        key=M + 2 * tA + tB, pad=pad, batch_pad=bpad)
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    ks.set_balanced_groups(per_cu)
+    for kid in balanced_ids(ks):
+        gpu.ensure_workspace(ks.workspace_bytes_needed(ks.F32, kid, M, N, batch))
+        plan = plan_of(ks, gpu, dp, kid)
+        ki = ks.kernel_info(ks.F32, kid)
+        groups = 256 * (per_cu or ki["balanced_per_cu"])
+        tiles = -(-M // ki["bm"]) * -(-N // ki["bn"]) * batch
+        assert plan["balanced_groups"] == groups and plan["divided_tiles"] == tiles % groups
+        assert plan["workgroups"] == groups and plan["split_k"] == 1
+        got = dp.run(kid)
+        check(p, got, ref, "balanced kernel %d %s tA=%d tB=%d" % (kid, shape[:4], tA, tB))
+        assert np.array_equal(got, dp.run(kid), equal_nan=True), "kernel %d: two runs differ" % kid
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+def test_balanced_form_small_integers_bit_exact(gpu, ks, tA, tB):
+    """Entries in [-8, 8] with K * 64 < 2^24: every partial sum is an integer fp32 holds exactly, so
+    the parts of a divided tile add up to the oracle's bits whatever the cut."""
+    p = wl.make_problem("f32", tA, tB, 1100, 1300, 520, batch=1, alpha=1.0, beta=0.0, seed=6,
+                        key=tA * 2 + tB, dist="ints", c_fill="nan", pad=(1, 0, 3))
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    live = ~c_padding_mask(p)
+    for per_cu in (1, 0):
+        ks.set_balanced_groups(per_cu)
+        for kid in balanced_ids(ks):
+            gpu.ensure_workspace(ks.workspace_bytes_needed(ks.F32, kid, p.M, p.N, p.batch))
+            assert np.array_equal(dp.run(kid)[live], ref[live]), "kernel %d per_cu %d" % (kid, per_cu)
+
+
+def test_without_scratch_the_plain_member_runs(gpu, ks):
+    p = wl.make_problem("f32", 0, 1, 1283, 964, 300, alpha=1.0, beta=0.25, seed=32)
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    try:
+        ks.set_workspace(None)
+        for kid in balanced_ids(ks):
+            plan = plan_of(ks, gpu, dp, kid)
+            assert plan["balanced_groups"] == 0 and plan["divided_tiles"] == 0
+            got = dp.run(kid)
+            check(p, got, ref, "kernel %d without scratch" % kid)
+            assert np.array_equal(got, dp.run(plain_twin(ks, kid)), equal_nan=True)
+    finally:
+        gpu.ensure_workspace.__defaults__[0].clear()      # the next test registers a fresh buffer
+
+
+def test_evenly_dividing_tile_count_needs_no_scratch(gpu, ks):
+    """256 tiles per round and nothing left over: the persistent form runs without a workspace and
+    every entry comes from one work-group, so it equals the plain member bit for bit."""
+    try:
+        ks.set_workspace(None)
+        ks.set_balanced_groups(1)
+        for kid in balanced_ids(ks):
+            ki = ks.kernel_info(ks.F32, kid)
+            M, N = 16 * ki["bm"], 32 * ki["bn"]           # 512 tiles: two rounds of 256 work-groups
+            p = wl.make_problem("f32", 0, 0, M, N, 136, alpha=-1.0, beta=0.0, seed=33, c_fill="nan")
+            dp = gpu.DeviceProblem(p)
+            plan = plan_of(ks, gpu, dp, kid)
+            assert plan["balanced_groups"] == 256 and plan["divided_tiles"] == 0
+            got = dp.run(kid)
+            bb, ii, jj = gpu.sample_entries(p, 300, 5, tile=ki["bm"])
+            ref = gpu.oracle_entries(p, bb, ii, jj)
+            vals = got.reshape(M, N)[ii, jj]
+            assert np.max(np.abs(vals - ref)) <= tolerance(p)
+            assert np.array_equal(got, dp.run(plain_twin(ks, kid)))
+    finally:
+        gpu.ensure_workspace.__defaults__[0].clear()
+
+
+def test_balanced_form_with_bias_and_bf16_output(gpu, ks):
+    import torch
+    from oracle import gemm as og
+    p = wl.make_problem("f32", 0, 0, 1283, 964, 300, batch=1, alpha=0.75, beta=0.5, seed=34)
+    dp = gpu.DeviceProblem(p)
+    bias = wl.uniform_pm1(p.N, 34, 9, 3)
+    dbias = torch.from_numpy(bias).cuda()
+    ref = p.C0.copy()
+    og.gemm_bias(p.dtype, p.transA, p.transB, p.M, p.N, p.K, p.alpha, p.A, p.lda, p.B, p.ldb, p.beta, ref, p.ldc,
+                 bias, p.batch, p.strideA, p.strideB, p.strideC)
+    ks.set_balanced_groups(1)
+    for kid in balanced_ids(ks):
+        gpu.ensure_workspace(ks.workspace_bytes_needed(ks.F32, kid, p.M, p.N, p.batch))
+        C = dp.C0.clone()
+        ks.gemm_bias(ks.F32, kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb, p.beta, C,
+                     p.ldc, dbias, p.batch, p.strideA, p.strideB, p.strideC)
+        torch.cuda.synchronize()
+        err = float(np.max(np.abs(C.cpu().numpy().astype(np.float64) - ref)))
+        tol = tolerance(p) + 2.0 ** -22 * (float(np.max(np.abs(bias))) + float(np.max(np.abs(ref))))
+        assert err <= tol, "kernel %d with bias: %.3e > %.3e" % (kid, err, tol)

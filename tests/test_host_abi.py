@@ -51,7 +51,8 @@ def test_registry_has_64_fp32_kernels_with_dense_ids():
                 assert ki["wm"] == ki["tm"] * f and ki["wn"] == ki["tn"] * f
                 assert ki["threads"] == 64 * (ki["bm"] // ki["wm"]) * (ki["bn"] // ki["wn"]) * ki["k_waves"]
             key = (dt, ki["core"], ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["split_k"], ki["k_waves"],
-                       ki["lds_bytes"], ki["band_rows"])   # LDS stages and tile order are parameters too
+                       ki["lds_bytes"], ki["band_rows"],   # LDS stages and tile order are parameters too
+                       ki["balanced_per_cu"])              # ... and so is the launch shape
             assert key not in seen, "duplicate instantiation %s" % (key,)
             seen.add(key)
     with pytest.raises(ks.KsError):

@@ -203,20 +203,27 @@ def config2_extra_rows(n=400, seed=11):
     return rows
 
 
-def large_fp32_rows(n=24, seed=16, lo=2048, hi=8192):
+def large_fp32_rows(n=24, seed=16, lo=2048, hi=8192, cap=2 ** 37):
     """Large fp32 GEMMs, for training the fp32 selector only (the tuning set stops at 4096 and holds
     few shapes that are large in all three dimensions): M, N, K log-uniform in [lo, hi], multiples
-    of 64, M*N*K at most 2^37; all four layouts."""
+    of 64, M*N*K at most `cap`; all four layouts."""
     r = np.random.default_rng(seed)
     rows, s = [], 0
     while s < n:
         M, N, K = (int(round(np.exp(r.uniform(np.log(lo), np.log(hi))) / 64.0)) * 64 for _ in range(3))
-        if M * N * K > 2 ** 37:
+        if M * N * K > cap:
             continue
         for tA, tB in itertools.product((0, 1), (0, 1)):
             rows.append((s, tA, tB, M, N, K, 1))
         s += 1
     return rows
+
+
+def medium_large_fp32_rows():
+    """72 more shapes between the top of the tuning set and the large ones (dimensions 1024 .. 8192,
+    M*N*K at most 2^36, seed 17): training rows for the pruning step, which otherwise sees too few
+    problems of several rounds of large tiles to give them a leaf of their own."""
+    return large_fp32_rows(n=72, seed=17, lo=1024, hi=8192, cap=2 ** 36)
 
 
 def config2_split(n=200, seed=1, train_fraction=0.7):
