@@ -300,12 +300,13 @@ int ks_calibration_copy(void *dst_device, const void *src_device, size_t bytes, 
  * device holds under matrix load depends on the bit patterns the instructions chew on).  2048
  * work-groups of eight waves load twelve 16-byte fragments per lane once from `operands_device`
  * (at least KS_MFMA_PROBE_BYTES, 16-byte aligned; pass the A operand of the GEMM in question) and
- * issue `rounds` x 32 dependent-free 32x32 MFMAs of `dtype` each, with no LDS or memory traffic.
+ * issue `rounds` x 32 dependent-free MFMAs of `dtype` each (fragment = 32: 32x32x16 for the 16-bit
+ * types, 32x32x2 for fp32; fragment = 16, 16-bit types only: 16x16x32), with no LDS or memory traffic.
  * Runs the kernel twice on `stream`, synchronises, and reports the second run: TFLOP/s from HIP
  * events and, if mhz_out != NULL, the shader clock of work-group 0 (cycle counter over the
  * 100 MHz reference counter).  1 <= rounds <= 2^24.  Not thread-safe against itself. */
 #define KS_MFMA_PROBE_BYTES (64u * 8u * 12u * 1024u)
-int ks_mfma_sustained(int dtype, const void *operands_device, size_t bytes, int rounds, void *stream,
+int ks_mfma_sustained(int dtype, int fragment, const void *operands_device, size_t bytes, int rounds, void *stream,
                       double *tflops_out, double *mhz_out);
 
 /* Measurement aid: the two-group 256 x 256 x 64 bf16 kernel on an NT problem (A: M x K, B: N x K,
@@ -315,12 +316,17 @@ int ks_mfma_sustained(int dtype, const void *operands_device, size_t bytes, int 
  *   mode 1  no direct-to-LDS global loads after the first two K-steps
  *   mode 2  no LDS fragment reads after the first two K-steps
  *   mode 3  neither (MFMAs, barriers and the C write only)
+ *   mode 4  the kernel of mode 0, whose work-group 0 also reads the shader cycle counter and the
+ *           100 MHz reference counter at both ends of its K loop: *mhz_out (host, required in
+ *           modes 4 and 5, ignored otherwise) receives the clock the device held during the last launch
+ *   mode 5  as mode 4 with 16x16x32 fragments instead of 32x32x16
  * For modes 1-3 the MFMAs run on the first K-steps' operands over and over: C is NOT a GEMM
  * result.  M, N multiples of 256, K a multiple of 64 and at least 128.  Two untimed launches, then
  * `iters` launches timed with HIP events one by one; ms_out[0 .. iters-1] (host) receives the
- * milliseconds.  Synchronises. */
+ * milliseconds.  Synchronises.  Not thread-safe against itself. */
 int ks_bf16_ablation(int mode, const uint16_t *A_device, const uint16_t *B_device, float *C_device,
-                     int64_t M, int64_t N, int64_t K, void *stream, int iters, float *ms_out);
+                     int64_t M, int64_t N, int64_t K, void *stream, int iters, float *ms_out,
+                     double *mhz_out);
 
 /* ---------------------------------------------------------------- workspace
  * Split-K kernels (K partitioned over work-groups, partial sums reduced in a fixed order, no

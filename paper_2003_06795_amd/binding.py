@@ -100,8 +100,8 @@ def lib():
     L.ks_set_selector.argtypes = [_i, _p, _i]
     L.ks_get_selector.argtypes = [_i, _p, _i]
     L.ks_calibration_copy.argtypes = [_p, _p, ctypes.c_size_t, _p]
-    L.ks_mfma_sustained.argtypes = [_i, _p, ctypes.c_size_t, _i, _p, _p, _p]
-    L.ks_bf16_ablation.argtypes = [_i, _p, _p, _p, _i64, _i64, _i64, _p, _i, _p]
+    L.ks_mfma_sustained.argtypes = [_i, _i, _p, ctypes.c_size_t, _i, _p, _p, _p]
+    L.ks_bf16_ablation.argtypes = [_i, _p, _p, _p, _i64, _i64, _i64, _p, _i, _p, _p]
     L.ks_set_fast_path.argtypes = [_i]
     L.ks_set_tiles_per_workgroup.argtypes = [_i]
     L.ks_set_balanced_groups.argtypes = [_i]
@@ -302,22 +302,25 @@ def calibration_copy(dst, src, nbytes, stream=None):
 MFMA_PROBE_BYTES = 64 * 8 * 12 * 1024
 
 
-def mfma_sustained(dtype, operands, nbytes=None, rounds=2000, stream=None):
-    """(TFLOP/s, shader MHz) of a pure MFMA loop on the values in `operands` (device buffer)."""
+def mfma_sustained(dtype, operands, nbytes=None, rounds=2000, stream=None, fragment=32):
+    """(TFLOP/s, shader MHz) of a pure MFMA loop on the values in `operands` (device buffer);
+    fragment 32: 32x32 MFMAs, 16 (16-bit types only): 16x16x32."""
     if nbytes is None:
         nbytes = operands.numel() * operands.element_size()
     tf, mhz = ctypes.c_double(0), ctypes.c_double(0)
-    _check(lib().ks_mfma_sustained(int(dtype), _dev(operands), int(nbytes), int(rounds), _stream(stream),
+    _check(lib().ks_mfma_sustained(int(dtype), int(fragment), _dev(operands), int(nbytes), int(rounds), _stream(stream),
                                    ctypes.byref(tf), ctypes.byref(mhz)), "ks_mfma_sustained")
     return tf.value, mhz.value
 
 
 def bf16_ablation(mode, A, B, C, M, N, K, iters=10, stream=None):
-    """Milliseconds of `iters` launches of the two-group bf16 kernel with data paths left out (mode 0-3)."""
+    """Milliseconds of `iters` launches of the two-group bf16 kernel with data paths left out (mode 0-3);
+    mode 4 is the whole kernel and returns (milliseconds, shader MHz during the last launch)."""
     out = np.zeros(iters, dtype=np.float32)
+    mhz = ctypes.c_double(0.0)
     _check(lib().ks_bf16_ablation(int(mode), _dev(A), _dev(B), _dev(C), M, N, K, _stream(stream), int(iters),
-                                  out.ctypes.data_as(_p)), "ks_bf16_ablation")
-    return out
+                                  out.ctypes.data_as(_p), ctypes.byref(mhz)), "ks_bf16_ablation")
+    return (out, float(mhz.value)) if int(mode) >= 4 else out
 
 
 def set_fast_path(enabled):

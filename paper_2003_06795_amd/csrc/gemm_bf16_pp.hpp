@@ -72,10 +72,15 @@ struct PpPlan {
     }
 };
 
-// ABLATE != 0 exists for measurement only (ks_bf16_ablation; the result is then not a GEMM): bit 0
-// leaves out the direct-to-LDS loads after the first two K-steps (LDS keeps their contents), bit 1
-// the LDS fragment reads after the first two K-steps (the registers keep theirs), so that the cost
-// of each data path can be read off against the full kernel on the same operand values.
+// ABLATE != 0 exists for measurement only (ks_bf16_ablation): bit 0 leaves out the direct-to-LDS
+// loads after the first two K-steps (LDS keeps their contents), bit 1 the LDS fragment reads after
+// the first two K-steps (the registers keep theirs), so that the cost of each data path can be read
+// off against the full kernel on the same operand values (the result is then not a GEMM).  Bit 2
+// changes nothing in the computation: the first lane of work-group 0 reads the shader cycle counter
+// and the 100 MHz reference counter at both ends of its K loop and leaves the differences in
+// pp_probe_clocks, which gives the clock the device holds while this kernel runs.
+static __device__ unsigned long long pp_probe_clocks[2];
+
 template <int F, bool SPLIT, bool AKC, bool BKC, bool F16 = false, int ABLATE = 0>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     constexpr int BM = 256, BN = 256, BK = 64, HALF = 128;
@@ -223,6 +228,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
 
     // A work-group whose K partition is empty (possible for the last split-K partition) only
     // writes zeros; the branch is uniform over the work-group, so the barriers stay matched.
+    unsigned long long probeC = 0, probeR = 0;
+    if constexpr ((ABLATE & 4) != 0) {
+        if (blockIdx.x == 0 && tid == 0) { probeC = __builtin_amdgcn_s_memtime(); probeR = __builtin_amdgcn_s_memrealtime(); }
+    }
     if (nk > 0) {
         // prologue: K-steps 0 and 1 except A1(1), in the order the waits count on
         const int s1 = min(1, nk - 1);
@@ -246,6 +255,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         // the loads issued past the end must have landed before this work-group's LDS is given away
         wait_vmcnt<0>();
         if (wr == 0) slot_end();                             // pairs with the second group's last slot
+    }
+    if constexpr ((ABLATE & 4) != 0) {
+        if (blockIdx.x == 0 && tid == 0) {
+            pp_probe_clocks[0] = __builtin_amdgcn_s_memtime() - probeC;
+            pp_probe_clocks[1] = __builtin_amdgcn_s_memrealtime() - probeR;
+        }
     }
 
 #pragma unroll
