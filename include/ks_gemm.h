@@ -318,10 +318,12 @@ int ks_mfma_sustained(int dtype, int fragment, const void *operands_device, size
  *   mode 3  neither (MFMAs, barriers and the C write only)
  *   mode 4  the kernel of mode 0, whose work-group 0 also reads the shader cycle counter and the
  *           100 MHz reference counter at both ends of its K loop: *mhz_out (host, required in
- *           modes 4 and 5, ignored otherwise) receives the clock the device held during the last launch
+ *           modes 4 to 6, ignored otherwise) receives the clock the device held during the last launch
  *   mode 5  as mode 4 with 16x16x32 fragments instead of 32x32x16
- * For modes 1-3 the MFMAs run on the first K-steps' operands over and over: C is NOT a GEMM
- * result.  M, N multiples of 256, K a multiple of 64 and at least 128.  Two untimed launches, then
+ *   mode 6  as mode 5, but every work-group fetches the operand panels of tile (0, 0): all loads
+ *           hit in L2 and nothing crosses the fabric (what the traffic beyond L2 costs)
+ * For modes 1-3 the MFMAs run on the first K-steps' operands over and over, and in mode 6 every
+ * tile is the product of the first panels: C is then NOT a GEMM result.  M, N multiples of 256, K a multiple of 64 and at least 128.  Two untimed launches, then
  * `iters` launches timed with HIP events one by one; ms_out[0 .. iters-1] (host) receives the
  * milliseconds.  Synchronises.  Not thread-safe against itself. */
 int ks_bf16_ablation(int mode, const uint16_t *A_device, const uint16_t *B_device, float *C_device,

@@ -33,9 +33,12 @@ template <int ROWS>
 struct Bf16LdsT {
     static constexpr int CPR = ROWS / 8;                    // 16-byte chunks per k row
     static constexpr int UPR = ROWS / 16;                   // 32-byte units per k row
-    // XOR applied to the 32-byte unit index of k row `k`
+    // XOR applied to the 32-byte unit index of k row `k`.  A transposing read touches, per group of
+    // sixteen lanes, one or two units of four consecutive k rows, and two such groups (k and k + 8
+    // with 16 x 16 fragments, the next sixteen tile rows with 32 x 32 fragments) are served
+    // together: bits 0, 1 and 3 of k pick the unit, so that all eight land in different banks.
     __device__ __forceinline__ static int swz(int k) {
-        if constexpr (UPR >= 8) return k & 7;
+        if constexpr (UPR >= 8) return (k & 3) | ((k >> 1) & 4);
         else if constexpr (UPR == 4) return (k >> 1) & 3;
         else if constexpr (UPR == 2) return (k >> 2) & 1;
         else return 0;

@@ -107,19 +107,22 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     const uint16_t *Ab = static_cast<const uint16_t *>(p.A) + (long long)tc.batch * p.strideA;
     const uint16_t *Bb = static_cast<const uint16_t *>(p.B) + (long long)tc.batch * p.strideB;
     float *Cb = p.C + (long long)tc.batch * p.strideC;
-    const char *aTile = reinterpret_cast<const char *>(AKC ? Ab + (long long)row0 * p.lda + kBegin
-                                                            : Ab + (long long)kBegin * p.lda + row0);
-    const char *bTile = reinterpret_cast<const char *>(BKC ? Bb + (long long)col0 * p.ldb + kBegin
-                                                            : Bb + (long long)kBegin * p.ldb + col0);
+    // measurement only (ABLATE bit 3): every work-group fetches the operand panels of tile (0, 0),
+    // so all loads hit in L2 and nothing crosses the fabric; the result is then not a GEMM
+    const int lrow0 = (ABLATE & 8) ? 0 : row0, lcol0 = (ABLATE & 8) ? 0 : col0;
+    const char *aTile = reinterpret_cast<const char *>(AKC ? Ab + (long long)lrow0 * p.lda + kBegin
+                                                            : Ab + (long long)kBegin * p.lda + lrow0);
+    const char *bTile = reinterpret_cast<const char *>(BKC ? Bb + (long long)lcol0 * p.ldb + kBegin
+                                                            : Bb + (long long)kBegin * p.ldb + lcol0);
     const long long aStep = AKC ? BK * 2LL : BK * 2LL * p.lda;
     const long long bStep = BKC ? BK * 2LL : BK * 2LL * p.ldb;
 
     PpPlan<AKC> pa0, pa1;
     PpPlan<BKC> pb0, pb1;
-    pa0.init(wave, lane, p.lda, row0, 0, p.M);
-    pa1.init(wave, lane, p.lda, row0, 1, p.M);
-    pb0.init(wave, lane, p.ldb, col0, 0, p.N);
-    pb1.init(wave, lane, p.ldb, col0, 1, p.N);
+    pa0.init(wave, lane, p.lda, lrow0, 0, p.M);
+    pa1.init(wave, lane, p.lda, lrow0, 1, p.M);
+    pb0.init(wave, lane, p.ldb, lcol0, 0, p.N);
+    pb1.init(wave, lane, p.ldb, lcol0, 1, p.N);
 
     // acc[i][j]: the wave's 64 x 32 block of quadrant (i, j)
     floatx4 acc16[2][2][F == 16 ? FM : 1][F == 16 ? FN : 1];

@@ -123,7 +123,7 @@ extern "C" int ks_mfma_sustained(int dtype, int fragment, const void *operands_d
 
 extern "C" int ks_bf16_ablation(int mode, const uint16_t *A, const uint16_t *B, float *C, int64_t M, int64_t N,
                                 int64_t K, void *stream, int iters, float *ms_out, double *mhz_out) {
-    if (mode < 0 || mode > 5 || !A || !B || !C || !ms_out || iters < 1 || iters > 1024) return KS_ERR_INVALID_ARG;
+    if (mode < 0 || mode > 6 || !A || !B || !C || !ms_out || iters < 1 || iters > 1024) return KS_ERR_INVALID_ARG;
     if (mode >= 4 && !mhz_out) return KS_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K < 128 || M % 256 || N % 256 || K % 64 || M > 65536 || N > 65536 || K > (1 << 22))
         return KS_ERR_INVALID_ARG;
@@ -150,7 +150,8 @@ extern "C" int ks_bf16_ablation(int mode, const uint16_t *A, const uint16_t *B, 
             case 2: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 2>), grid, block, 0, s, p); break;
             case 3: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 3>), grid, block, 0, s, p); break;
             case 4: hipLaunchKernelGGL((gemm_bf16_pp_kernel<32, false, true, true, false, 4>), grid, block, 0, s, p); break;
-            default: hipLaunchKernelGGL((gemm_bf16_pp_kernel<16, false, true, true, false, 4>), grid, block, 0, s, p); break;
+            case 5: hipLaunchKernelGGL((gemm_bf16_pp_kernel<16, false, true, true, false, 4>), grid, block, 0, s, p); break;
+            default: hipLaunchKernelGGL((gemm_bf16_pp_kernel<16, false, true, true, false, 12>), grid, block, 0, s, p); break;
         }
         float ms = 0.f;
         if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess ||

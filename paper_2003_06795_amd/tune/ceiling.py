@@ -54,6 +54,7 @@ def main():
     out["kernel_clock"] = {}
     for operands, mode, (X, Y), (tf_only, mhz_only) in (("normal_operands", 4, (A, B), (tf1, mhz1)),
                                                         ("normal_operands_16x16x32", 5, (A, B), (tf16, mhz16)),
+                                                        ("normal_operands_16x16x32_all_loads_hit_L2", 6, (A, B), (tf16, mhz16)),
                                                         ("zero_operands", 4, (Z, Z), (tf0, mhz0))):
         ms4, mhz = ks.bf16_ablation(mode, X, Y, C, n, n, n, iters=a.iters)
         ms4 = float(np.median(ms4))

@@ -6,7 +6,9 @@
 Prints the kernel symbols by total time until `share` of the kernel time is covered.  With --bench
 (the JSON line bench.py printed in the profiled run) the row of the line's roofline kernel is
 always printed, marked, with the TFLOP/s that follows from its average duration and the line's
-flops per launch, so that the line's `roofline.frac` can be recomputed from this file alone.
+flops per launch, so that the line's `roofline.frac` can be recomputed from this file alone; the
+second kernel of the balanced persistent form (which shares the timed interval of its GEMM in the
+bench line) is always printed too.
 """
 import argparse
 import csv
@@ -37,7 +39,7 @@ def main(argv=None):
     for r in rows:
         name = short(r["Name"])
         is_roof = roof is not None and name.startswith(roof["kernel"].rstrip(">"))
-        if (cum < a.share * total and shown < a.max_rows) or is_roof:
+        if (cum < a.share * total and shown < a.max_rows) or is_roof or "sk_fixup" in name:
             print("%-100s %8d %12.3f %10.3f %6.2f%s" % (name[:100], int(r["Calls"]), float(r["TotalDurationNs"]) / 1e6,
                                                        float(r["AverageNs"]) / 1e3,
                                                        100.0 * float(r["TotalDurationNs"]) / total,
