@@ -31,7 +31,8 @@
  *     called from several host threads (each on its own stream) at once, with
  *     one exception: the registered workspace is a single buffer, so two GEMMs
  *     that both run a split-K member must not be in flight together (same
- *     stream, or ordered by the caller).  ks_set_workspace, ks_set_fast_path,
+ *     stream, or ordered by the caller); ks_gemm_with_workspace takes the
+ *     scratch per call and has no such limit.  ks_set_workspace, ks_set_fast_path,
  *     ks_set_tiles_per_workgroup, ks_set_balanced_groups,
  *     ks_set_selector and ks_time_gemm are not thread-safe.  The library acts
  *     on the calling thread's current HIP device and never changes it.
@@ -206,6 +207,20 @@ int ks_gemm_static_scratch(int dtype, int kernel_id, int transA, int transB, int
                            float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
                            float beta, float *C, int64_t ldc,
                            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, void *stream);
+
+/* The same GEMM with the scratch passed per call instead of registered: ks_gemm_*_with_kernel
+ * (kernel_id >= 0) or ks_gemm_* (kernel_id < 0, with the same fallback to the split_k == 1 twin when
+ * the scratch is too small) using `workspace_device` (device pointer, at least 4-byte aligned; may
+ * be NULL with workspace_bytes == 0) for split-K partial sums and for the divided tiles of the
+ * balanced persistent form.  The registered workspace is neither read nor needed, so GEMMs on
+ * different streams or host threads that each bring their own scratch may be in flight together
+ * (Section II-A's tuner times one cell at a time; a serving process does not).  Needs what
+ * ks_workspace_bytes_needed reports for the member; errors as for ks_gemm_*. */
+int ks_gemm_with_workspace(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                           float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                           float beta, float *C, int64_t ldc,
+                           int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                           void *workspace_device, size_t workspace_bytes, void *stream);
 
 /* What a GEMM call would launch, without launching it: the same checks and decisions as
  * ks_gemm_*_with_kernel (kernel_id >= 0) or ks_gemm_* (kernel_id < 0) with the workspace that is

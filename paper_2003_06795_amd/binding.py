@@ -60,7 +60,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
-    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_bf16_ablation", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
+    "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_with_workspace", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_bf16_ablation", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
     "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_balanced_groups", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_performance", "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans", "ks_tune_prune_hdbscan",
@@ -91,6 +91,7 @@ def lib():
     L.ks_gemm_bias.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
     L.ks_gemm_out_bf16.argtypes = [_i, _i] + _GEMM[:13] + [_p] + _GEMM[13:]
     L.ks_gemm_static_scratch.argtypes = [_i, _i] + _GEMM
+    L.ks_gemm_with_workspace.argtypes = [_i, _i] + _GEMM[:-1] + [_p, ctypes.c_size_t, _p]
     L.ks_gemm_plan.argtypes = [_i, _i] + _GEMM[:-1] + [ctypes.POINTER(LaunchPlan)]
     L.ks_time_gemm.argtypes = [_i, _i] + _GEMM + [_i, _i, _i, _p]
     L.ks_num_kernels.argtypes = [_i]
@@ -226,6 +227,18 @@ def gemm_static_scratch(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda
     _check(lib().ks_gemm_static_scratch(
         int(dtype), int(kernel_id), *_gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
                                                 batch, strideA, strideB, strideC, stream)), "ks_gemm_static_scratch")
+
+
+def gemm_with_workspace(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                        workspace, batch=1, strideA=0, strideB=0, strideC=0, stream=None):
+    """GEMM whose scratch (split-K partial sums, divided tiles) is `workspace` (torch tensor or None),
+    not the registered one."""
+    a = _gemm_args(transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, batch, strideA, strideB,
+                   strideC, stream)
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().ks_gemm_with_workspace(int(dtype), int(kernel_id), *a[:-1],
+                                        _dev(workspace) if workspace is not None else None, nbytes, a[-1]),
+           "ks_gemm_with_workspace")
 
 
 def gemm_plan(dtype, kernel_id, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,

@@ -702,6 +702,22 @@ extern "C" int ks_gemm_static_scratch(int dtype, int kernel_id, int transA, int 
     return run_ws(w, dtype, kernel_id, KS_GEMM_PASS);
 }
 
+extern "C" int ks_gemm_with_workspace(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N,
+                                      int64_t K, float alpha, const void *A, int64_t lda, const void *B,
+                                      int64_t ldb, float beta, float *C, int64_t ldc, int64_t batch,
+                                      int64_t strideA, int64_t strideB, int64_t strideC, void *workspace_device,
+                                      size_t workspace_bytes, void *stream) {
+    if (dtype != KS_F32 && dtype != KS_BF16 && dtype != KS_F16) return KS_ERR_INVALID_ARG;
+    if ((workspace_device == nullptr) != (workspace_bytes == 0)) return KS_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace_device) % sizeof(float)) return KS_ERR_INVALID_ARG;
+    const Workspace w{workspace_device, workspace_bytes};
+    if (kernel_id < 0) {
+        kernel_id = select_checked(dtype, M, N, K, batch, transA, transB, w);
+        if (kernel_id < 0) return kernel_id;
+    }
+    return run_ws(w, dtype, kernel_id, KS_GEMM_PASS);
+}
+
 extern "C" int ks_gemm_plan(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
                             float alpha, const void *A, int64_t lda, const void *B, int64_t ldb, float beta,
                             float *C, int64_t ldc, int64_t batch, int64_t strideA, int64_t strideB,

@@ -177,3 +177,28 @@ def test_balanced_form_with_bias_and_bf16_output(gpu, ks):
         err = float(np.max(np.abs(C.cpu().numpy().astype(np.float64) - ref)))
         tol = tolerance(p) + 2.0 ** -22 * (float(np.max(np.abs(bias))) + float(np.max(np.abs(ref))))
         assert err <= tol, "kernel %d with bias: %.3e > %.3e" % (kid, err, tol)
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+def test_balanced_form_at_full_size(gpu, ks, tA, tB):
+    """The largest shape of the fp32 tuning set (3016 x 1448 x 3656: 288 tiles of 128 x 128 on 512
+    work-groups, 1104 tiles of 64 x 64 on 768) in the launch bench.py times: the members take the
+    balanced form by themselves; sampled entries against the oracle."""
+    import torch
+    M, N, K = 3016, 1448, 3656
+    p = wl.make_problem("f32", tA, tB, M, N, K, seed=35, key=tA * 2 + tB, c_fill="zeros")
+    A, B = torch.from_numpy(p.A).cuda(), torch.from_numpy(p.B).cuda()
+    bb, ii, jj = gpu.sample_entries(p, 1024, 35, tile=128)
+    ref = gpu.oracle_entries(p, bb, ii, jj)
+    flat = torch.from_numpy(ii * p.ldc + jj).cuda()
+    for kid in balanced_ids(ks):
+        gpu.ensure_workspace(ks.workspace_bytes_needed(ks.F32, kid, M, N, 1))
+        C = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+        args = (tA, tB, M, N, K, 1.0, A, p.lda, B, p.ldb, 0.0, C, p.ldc)
+        plan = ks.gemm_plan(ks.F32, kid, *args)
+        assert plan["balanced_groups"] > 0 and plan["divided_tiles"] > 0, (kid, plan)
+        ks.gemm_f32_with_kernel(kid, *args)
+        torch.cuda.synchronize()
+        assert not bool(torch.isnan(C).any()), "kernel %d left entries unwritten" % kid
+        err = float(np.max(np.abs(C[flat].cpu().numpy().astype(np.float64) - ref)))
+        assert err <= tolerance(p), "kernel %d: %.3e > %.3e" % (kid, err, tolerance(p))

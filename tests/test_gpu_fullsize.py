@@ -179,12 +179,13 @@ def test_every_kept_bf16_kernel_general_path_at_ragged_sizes(gpu):
 
 @pytest.mark.parametrize("N", [512, 2048])
 def test_config3_workhorse_kernels_beyond_4_gib(gpu, N):
-    """A = 401408 x 4608 fp32 (7.4 GB): ids 59 (128 x 128 x 32) and 29 (64 x 64 x 32), the members the
-    deployed tree gives the im2col rows of this size."""
+    """A = 401408 x 4608 fp32 (7.4 GB): ids 59 and 47 (128 x 128 x 32, plain and with a balanced form
+    that such tile counts do not take) and 29 (64 x 64 x 32), the members the deployed trees have
+    given the im2col rows of this size."""
     M, K = 401408, 4608
     p = wl.make_problem("f32", 0, 0, M, N, K, seed=2, key=N, c_fill="zeros")
     assert p.A.nbytes > 2 ** 32
-    for kid in ((59, 29) if N == 512 else (59,)):
+    for kid in ((59, 47, 29) if N == 512 else (59, 47)):
         run_forced_and_check(gpu, p, kid, 1024, N + kid, "fp32 id %d, 401408 x %d x 4608" % (kid, N))
 
 
