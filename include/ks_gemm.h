@@ -32,10 +32,12 @@
  *     one exception: the registered workspace is a single buffer, so two GEMMs
  *     that both run a split-K member must not be in flight together (same
  *     stream, or ordered by the caller); ks_gemm_with_workspace takes the
- *     scratch per call and has no such limit.  ks_set_workspace, ks_set_fast_path,
- *     ks_set_tiles_per_workgroup, ks_set_balanced_groups,
- *     ks_set_selector and ks_time_gemm are not thread-safe.  The library acts
- *     on the calling thread's current HIP device and never changes it.
+ *     scratch per call and has no such limit.  ks_set_workspace,
+ *     ks_set_fast_path, ks_set_tiles_per_workgroup, ks_set_balanced_groups and
+ *     ks_set_selector are not thread-safe: they change process-wide settings
+ *     that the compute entry points read.  ks_time_gemm keeps its events per
+ *     host thread.  The library acts on the calling thread's current HIP device
+ *     and never changes it.
  */
 #ifndef KS_GEMM_H
 #define KS_GEMM_H

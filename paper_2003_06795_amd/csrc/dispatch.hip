@@ -744,8 +744,9 @@ extern "C" int ks_time_gemm(int dtype, int kernel_id, int transA, int transB, in
         if (kernel_id < 0) return kernel_id;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    static hipEvent_t ev[2 * 1024];
-    static int evCount = 0;
+    // one pool of events per host thread (events are created once and reused by later calls)
+    static thread_local hipEvent_t ev[2 * 1024];
+    static thread_local int evCount = 0;
     while (evCount < 2 * iters) {
         if (hipEventCreate(&ev[evCount]) != hipSuccess) return KS_ERR_LAUNCH;
         ++evCount;
