@@ -65,7 +65,7 @@ def kernel_symbol(ks, dt, plan, tA, tB):
             b(plan["tiles_per_workgroup"] > 1), b(plan["balanced_groups"] > 0))
     f = 16 if ki["core_name"] == "mfma16" else 32
     if plan["path"] == 2:
-        return "gemm_bf16_pp_kernel<%d, %s, %s, %s, false, 0>" % (f, b(split), b(akc), b(bkc))
+        return "gemm_bf16_pp_kernel<%d, %s, %s, %s, false, 0, %d, %d>" % (f, b(split), b(akc), b(bkc), ki["bm"], ki["bk"])
     if plan["path"] == 1:
         stages = ki["lds_bytes"] // (ki["bk"] * (ki["bm"] + ki["bn"]) * 2)
         return "gemm_bf16_dma_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %s, false>" % (

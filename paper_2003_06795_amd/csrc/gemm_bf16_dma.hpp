@@ -29,7 +29,8 @@ namespace ks {
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-template <int ROWS>
+// F: fragment edge of the MFMAs that read the tile (the unit swizzle of narrow tiles depends on it)
+template <int ROWS, int F = 32>
 struct Bf16LdsT {
     static constexpr int CPR = ROWS / 8;                    // 16-byte chunks per k row
     static constexpr int UPR = ROWS / 16;                   // 32-byte units per k row
@@ -39,8 +40,12 @@ struct Bf16LdsT {
     // together: bits 0, 1 and 3 of k pick the unit, so that all eight land in different banks.
     __device__ __forceinline__ static int swz(int k) {
         if constexpr (UPR >= 8) return (k & 3) | ((k >> 1) & 4);
-        else if constexpr (UPR == 4) return (k >> 1) & 3;
-        else if constexpr (UPR == 2) return (k >> 2) & 1;
+        // narrower tiles: 16 x 16 fragments read k and k + 8 in the same pass, and a k row of 128 or
+        // 64 bytes already puts k and k + 1 into different banks: the units tell k from k + 2 and
+        // from k + 8.  32 x 32 fragments read two units of four consecutive k rows per pass and
+        // keep the pairing that measured fastest for them (the other one cost them 5 - 20 %).
+        else if constexpr (UPR == 4) return F == 16 ? ((k & 2) | ((k >> 3) & 1)) : ((k >> 1) & 3);
+        else if constexpr (UPR == 2) return F == 16 ? ((k >> 3) & 1) : ((k >> 2) & 1);
         else return 0;
     }
     // byte offset of element (k, row) for row a multiple of 4
@@ -50,7 +55,7 @@ struct Bf16LdsT {
 };
 
 // Per-lane source offsets of the direct-to-LDS loads of one operand tile.
-template <int ROWS, int BK, int NW, bool KC>
+template <int ROWS, int BK, int NW, bool KC, int F = 32>
 struct DmaPlan {
     static constexpr int TOTAL = ROWS * BK / 512;            // 1 KiB instructions per tile
     static constexpr int PER_WAVE = (TOTAL + NW - 1) / NW;
@@ -70,7 +75,7 @@ struct DmaPlan {
             } else {
                 constexpr int CPR = ROWS / 8;
                 const int k = L / CPR, pos = L % CPR;
-                const int c = pos ^ (2 * Bf16LdsT<ROWS>::swz(k));
+                const int c = pos ^ (2 * Bf16LdsT<ROWS, F>::swz(k));
                 const int row = min(row0 + c * 8, limit - 8) - row0;
                 off[j] = (unsigned)(((long long)k * ld + row) * 2);
             }
@@ -110,7 +115,7 @@ __device__ __forceinline__ bf16x8 read_fragment(const char *tile, int rowBase, i
             tile + 16 * Bf16Lds<BK>::chunk(rowBase + lane % F, kk / 8 + lgrp)));
     } else {
         typedef short shortx8 __attribute__((ext_vector_type(8)));
-        using LT = Bf16LdsT<ROWS>;
+        using LT = Bf16LdsT<ROWS, F>;
         const int trRow = 4 * (lane & 3) + (F == 32 ? 16 * ((lane >> 4) & 1) : 0);
         const int kb = kk + 8 * lgrp + ((lane & 15) >> 2);
         const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -173,8 +178,8 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN)) void gemm_bf16_dma_kern
     const long long aStep = AKC ? BK * 2LL : BK * 2LL * p.lda;
     const long long bStep = BKC ? BK * 2LL : BK * 2LL * p.ldb;
 
-    DmaPlan<BM, BK, NW, AKC> pa;
-    DmaPlan<BN, BK, NW, BKC> pb;
+    DmaPlan<BM, BK, NW, AKC, F> pa;
+    DmaPlan<BN, BK, NW, BKC, F> pb;
     pa.init(wave, lane, p.lda, row0, p.M);
     pb.init(wave, lane, p.ldb, col0, p.N);
 

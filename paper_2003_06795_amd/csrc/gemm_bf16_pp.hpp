@@ -1,5 +1,8 @@
-// 256 x 256 x 64 member of the 16-bit family (paper Section II: one work-group tile, wave tile and
-// K-step of the templated kernel) in its "two groups of waves" form for gfx950.
+// 256 x 256 x 64 and 128 x 128 x 128 members of the 16-bit family (paper Section II: one work-group
+// tile, wave tile and K-step of the templated kernel) in their "two groups of waves" form for
+// gfx950.  The description below uses the numbers of the 256 x 256 x 64 tile; the 128 x 128 x 128
+// tile (TILE = 128, BK = 128: 64-row halves of the same 16 KB, 32 x 16 blocks per wave and quadrant,
+// 16x16x32 fragments only, 256 matrix-pipe clocks per compute slot) runs the same schedule.
 //
 // The eight waves of a work-group form two groups of four; a SIMD holds one wave of each group.
 // Every K-step is cut into two pairs of slots, a memory slot (LDS -> register fragment reads and
@@ -34,22 +37,25 @@ namespace ks {
 
 // Per-lane source offsets (bytes from the tile origin, row0 / col0 at this K-step) of the two
 // direct-to-LDS loads a wave contributes to one 128-row half of an operand tile.
-template <bool KC>
+template <bool KC, int HALF = 128, int BK = 64, int F = 32>
 struct PpPlan {
+    static_assert(HALF * BK == 8192, "a half tile is 16 KB: sixteen 1 KB loads, two per wave");
     unsigned off[2];
     __device__ __forceinline__ void init(int wave, int lane, long long ld, int row0, int half, int limit) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int L = (wave + j * 8) * 64 + lane;            // 16-byte slot in the LDS half
             if constexpr (KC) {
-                const int r = L >> 3, pos = L & 7;
-                const int c = pos ^ ((r >> 1) & 7);
-                const int row = min(row0 + half * 128 + r, limit - 1) - row0;
+                constexpr int CPR = BK / 8, RP = 16 / CPR;       // as in Bf16Lds<BK>::chunk
+                const int r = L / CPR, pos = L % CPR;
+                const int c = pos ^ ((r / RP) & (CPR - 1));
+                const int row = min(row0 + half * HALF + r, limit - 1) - row0;
                 off[j] = (unsigned)(((long long)row * ld + c * 8) * 2);
             } else {
-                const int k = L >> 4, pos = L & 15;
-                const int c = pos ^ (2 * Bf16LdsT<128>::swz(k));
-                const int row = min(row0 + half * 128 + c * 8, limit - 8) - row0;
+                constexpr int CPK = HALF / 8;                    // 16-byte chunks per k row
+                const int k = L / CPK, pos = L % CPK;
+                const int c = pos ^ (2 * Bf16LdsT<HALF, F>::swz(k));
+                const int row = min(row0 + half * HALF + c * 8, limit - 8) - row0;
                 off[j] = (unsigned)(((long long)k * ld + row) * 2);
             }
         }
@@ -81,10 +87,12 @@ struct PpPlan {
 // pp_probe_clocks, which gives the clock the device holds while this kernel runs.
 static __device__ unsigned long long pp_probe_clocks[2];
 
-template <int F, bool SPLIT, bool AKC, bool BKC, bool F16 = false, int ABLATE = 0>
+template <int F, bool SPLIT, bool AKC, bool BKC, bool F16 = false, int ABLATE = 0, int TILE = 256, int BK = 64>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
-    constexpr int BM = 256, BN = 256, BK = 64, HALF = 128;
-    constexpr int FM = 64 / F, FN = 32 / F;                  // fragments of a wave's 64 x 32 block
+    static_assert((TILE == 256 && BK == 64) || (TILE == 128 && BK == 128 && F == 16), "tiles of this form");
+    constexpr int BM = TILE, BN = TILE, HALF = TILE / 2;
+    constexpr int WBM = HALF / 2, WBN = HALF / 4;            // a wave's block of one quadrant: 64 x 32 or 32 x 16
+    constexpr int FM = WBM / F, FN = WBN / F;                // its fragments
     constexpr int KSTEP = F == 32 ? 16 : 32, NSUB = BK / KSTEP;
     constexpr int HB = HALF * BK * 2;                        // bytes of one half tile
     __shared__ __attribute__((aligned(1024))) char A00[HB];  // A<stage><half>
@@ -117,14 +125,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     const long long aStep = AKC ? BK * 2LL : BK * 2LL * p.lda;
     const long long bStep = BKC ? BK * 2LL : BK * 2LL * p.ldb;
 
-    PpPlan<AKC> pa0, pa1;
-    PpPlan<BKC> pb0, pb1;
+    PpPlan<AKC, HALF, BK, F> pa0, pa1;
+    PpPlan<BKC, HALF, BK, F> pb0, pb1;
     pa0.init(wave, lane, p.lda, lrow0, 0, p.M);
     pa1.init(wave, lane, p.lda, lrow0, 1, p.M);
     pb0.init(wave, lane, p.ldb, lcol0, 0, p.N);
     pb1.init(wave, lane, p.ldb, lcol0, 1, p.N);
 
-    // acc[i][j]: the wave's 64 x 32 block of quadrant (i, j)
+    // acc[i][j]: the wave's block of quadrant (i, j)
     floatx4 acc16[2][2][F == 16 ? FM : 1][F == 16 ? FN : 1];
     floatx16 acc32[2][2][F == 32 ? FM : 1][F == 32 ? FN : 1];
 #pragma unroll
@@ -156,14 +164,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
         for (int m = 0; m < FM; ++m)
 #pragma unroll
             for (int ks = 0; ks < NSUB; ++ks)
-                a[m][ks] = read_fragment<F, HALF, BK, AKC>(half, wr * 64 + m * F, ks * KSTEP, lane);
+                a[m][ks] = read_fragment<F, HALF, BK, AKC>(half, wr * WBM + m * F, ks * KSTEP, lane);
     };
     auto read_b = [&](const char *half, bf16x8 (&b)[FN][NSUB]) {
 #pragma unroll
         for (int n = 0; n < FN; ++n)
 #pragma unroll
             for (int ks = 0; ks < NSUB; ++ks)
-                b[n][ks] = read_fragment<F, HALF, BK, BKC>(half, wc * 32 + n * F, ks * KSTEP, lane);
+                b[n][ks] = read_fragment<F, HALF, BK, BKC>(half, wc * WBN + n * F, ks * KSTEP, lane);
     };
     auto mma = [&](auto qi, auto qj, const bf16x8 (&b)[FN][NSUB]) {
         constexpr int QI = decltype(qi)::value, QJ = decltype(qj)::value;
@@ -270,10 +278,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const GemmParams p) {
     for (int q = 0; q < 4; ++q) {
         const int i = q >> 1, j = q & 1;
         if constexpr (F == 16)
-            write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + i * HALF + wr * 64, col0 + j * HALF + wc * 32, lane,
+            write_tile_mfma16<SPLIT, FM, FN>(p, tc, Cb, row0 + i * HALF + wr * WBM, col0 + j * HALF + wc * WBN, lane,
                                              acc16[i][j]);
         else
-            write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + i * HALF + wr * 64, col0 + j * HALF + wc * 32, lane,
+            write_tile_mfma32<SPLIT, FM, FN>(p, tc, Cb, row0 + i * HALF + wr * WBM, col0 + j * HALF + wc * WBN, lane,
                                              acc32[i][j]);
     }
 }

@@ -10,8 +10,9 @@
 
 namespace ks {
 
-// The eight-wave 256 x 256 x 64 members (128 x 64 of output per wave) run in the form with two
-// groups of waves alternating between memory and MFMA slots (gemm_bf16_pp.hpp).
+// The eight-wave 256 x 256 x 64 members (128 x 64 of output per wave) and the eight-wave
+// 128 x 128 x 128 members on 16x16x32 fragments run in the form with two groups of waves
+// alternating between memory and MFMA slots (gemm_bf16_pp.hpp).
 template <int F, int BM, int BN, int BK, int WM, int WN, int STAGES>
 constexpr bool kTwoGroups = bf16_two_groups(F, BM, BN, BK, WM, WN, STAGES);
 
@@ -24,8 +25,8 @@ static void launch_bf16_dma_fixed(const GemmParams &p, int grid, int variant, hi
 #define KS_V(A, B)                                                                                                  \
     do {                                                                                                            \
         if constexpr (kTwoGroups<F, BM, BN, BK, WM, WN, STAGES>) {                                                  \
-            if (variant & 16) hipLaunchKernelGGL((gemm_bf16_pp_kernel<F, SPLIT, A, B, true>), g, b, 0, s, p);       \
-            else hipLaunchKernelGGL((gemm_bf16_pp_kernel<F, SPLIT, A, B, false>), g, b, 0, s, p);                   \
+            if (variant & 16) hipLaunchKernelGGL((gemm_bf16_pp_kernel<F, SPLIT, A, B, true, 0, BM, BK>), g, b, 0, s, p);  \
+            else hipLaunchKernelGGL((gemm_bf16_pp_kernel<F, SPLIT, A, B, false, 0, BM, BK>), g, b, 0, s, p);        \
         } else if (variant & 16)                                                                                    \
             hipLaunchKernelGGL((gemm_bf16_dma_kernel<F, BM, BN, BK, WM, WN, STAGES, SPLIT, A, B, true>), g, b, 0, s, p);  \
         else                                                                                                        \

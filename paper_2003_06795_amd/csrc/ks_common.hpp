@@ -70,10 +70,12 @@ constexpr bool f32_multi_tile(int core, int bm, int bn, int p1, int p2, int kw) 
 }
 
 // 16-bit members whose direct-to-LDS path runs in the form with two groups of waves alternating
-// between memory and MFMA slots: the eight-wave 256 x 256 x 64 members (128 x 64 of output per wave),
-// with either fragment shape.
+// between memory and MFMA slots: the eight-wave 256 x 256 x 64 members (128 x 64 of output per wave)
+// with either fragment shape, and the eight-wave 128 x 128 x 128 members on 16x16x32 fragments
+// (64 x 32 of output per wave).
 constexpr bool bf16_two_groups(int f, int bm, int bn, int bk, int wm, int wn, int stages) {
-    return (f == 32 || f == 16) && bm == 256 && bn == 256 && bk == 64 && wm == 128 && wn == 64 && stages == 2;
+    return ((f == 32 || f == 16) && bm == 256 && bn == 256 && bk == 64 && wm == 128 && wn == 64 && stages == 2) ||
+           (f == 16 && bm == 128 && bn == 128 && bk == 128 && wm == 64 && wn == 32 && stages == 2);
 }
 
 // launch shape that tile_of_block expects

@@ -35,7 +35,7 @@ constexpr bool compiled_bf16(int) { return true; }
 #endif
 
 constexpr int kNumF32 = 64;
-constexpr int kNumBf16 = 46;
+constexpr int kNumBf16 = 48;
 constexpr int kShards = 16;
 
 }  // namespace ks

@@ -1,5 +1,6 @@
-"""GPU parity of the 256 x 256 x 64 eight-wave 16-bit members in their two-groups-of-waves form
-(bf16 ids 2, 20, 25 on 32x32x16 fragments, 44 and 45 on 16x16x32 fragments): against the CPU oracle within the stated bound, and bit for bit against the
+"""GPU parity of the eight-wave 16-bit members in their two-groups-of-waves form (256 x 256 x 64:
+bf16 ids 2, 20, 25 on 32x32x16 fragments, 44 and 45 on 16x16x32 fragments; 128 x 128 x 128: ids 46
+and 47): against the CPU oracle within the stated bound, and bit for bit against the
 generic path of the same members (same tiles, same summation order per entry).  Covers the edge
 cases of that kernel's own structure: one K-step, odd and even step counts, an empty last split-K
 partition, tiles whose second 128-row half lies wholly outside the matrix, all four layouts, both
@@ -15,7 +16,8 @@ pytestmark = pytest.mark.gpu
 LAYOUTS = [(0, 0), (0, 1), (1, 0), (1, 1)]
 PLAIN, SPLIT4, PERCALL = 2, 20, 25
 PLAIN16, PERCALL16 = 44, 45           # the same form on 16x16x32 fragments
-plain_members = pytest.mark.parametrize("plain", [PLAIN, PLAIN16])
+PLAIN128, PERCALL128 = 46, 47         # ... and on a 128 x 128 x 128 tile
+plain_members = pytest.mark.parametrize("plain", [PLAIN, PLAIN16, PLAIN128])
 
 
 @pytest.fixture(scope="module")
@@ -56,13 +58,18 @@ def test_members_exist_as_described(gpu):
         ki = ks.kernel_info(ks.BF16, kid)
         assert (ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["threads"], ki["split_k"], ki["core_name"]) == \
                (256, 256, 64, 128, 64, 512, split, core)
+    for kid, split in ((PLAIN128, 1), (PERCALL128, 0)):
+        ki = ks.kernel_info(ks.BF16, kid)
+        assert (ki["bm"], ki["bn"], ki["bk"], ki["wm"], ki["wn"], ki["threads"], ki["split_k"], ki["core_name"]) == \
+               (128, 128, 128, 64, 32, 512, split, "mfma16")
 
 
 @plain_members
 @pytest.mark.parametrize("tA,tB", LAYOUTS)
-@pytest.mark.parametrize("K", [64, 128, 192, 448, 1024])
+@pytest.mark.parametrize("K", [64, 128, 192, 448, 1024, 384, 896])
 def test_step_counts_and_layouts(gpu, tA, tB, K, plain):
-    """1, 2, 3, 7 and 16 K-steps; 520 x 776 spans three tiles each way with ragged edges."""
+    """1, 2, 3, 7 and 16 K-steps of 64 (1, 3, 7 and 8 of 128; K that is not a multiple of the
+    member's K-step takes its general kernel); 520 x 776 spans several tiles each way with ragged edges."""
     p = wl.make_problem("bf16", tA, tB, 520, 776, K, alpha=1.0, beta=0.0, seed=31, key=K + tA * 2 + tB,
                         dist="normal", c_fill="nan")
     check(gpu, p, plain, "bf16 id %d, K %d layout %d%d" % (plain, K, tA, tB))
@@ -100,6 +107,7 @@ def test_split_k_with_an_empty_last_partition(gpu, tA, tB):
     check(gpu, p, SPLIT4, "bf16 id 20 (split 4), K 8192")
     check(gpu, p, PERCALL, "bf16 id 25 (split per call), K 8192")
     check(gpu, p, PERCALL16, "bf16 id 45 (split per call, 16x16x32 fragments), K 8192")
+    check(gpu, p, PERCALL128, "bf16 id 47 (split per call, 128 x 128 x 128 tile), K 8192")
 
 
 @plain_members
