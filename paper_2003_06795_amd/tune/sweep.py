@@ -1,6 +1,6 @@
 """Brute-force timing sweep (paper Section II-A): every kernel of the family on every workload.
 
-    python -m paper_2003_06795_amd.tune.sweep --config 2 --out gpurun_out/timings_cfg2.csv
+    python -m paper_2003_06795_amd.tune.sweep --config 2 --out timings_cfg2.csv
 
 Each (workload, kernel) cell is timed inside the library (ks_time_gemm: HIP events around
 back-to-back launches on the stream) with `--warmup` untimed launches and `--iters` samples whose
