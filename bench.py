@@ -281,7 +281,12 @@ def time_set(ks, torch, workload, iters=10):
             plan = ks.gemm_plan(dt, -1, *args)
             fl = 2.0 * r["M"] * r["N"] * r["K"] * r["batch"]
             reps = int(min(64, max(1, np.ceil(1.2e9 / fl))))
-            t = float(np.median(ks.time_gemm(dt, -1, *args, warmup=2, iters=iters, reps=reps)))
+            # the clock the device holds settles over some tens of milliseconds of load (the first
+            # cell measured after the buffers were filled reads several per cent low otherwise):
+            # a first estimate sizes about 30 ms of untimed launches before the timed samples
+            est = float(np.median(ks.time_gemm(dt, -1, *args, warmup=1, iters=3, reps=reps)))
+            warm = int(min(64, max(2, np.ceil(30.0 / max(est * reps, 1e-3)))))
+            t = float(np.median(ks.time_gemm(dt, -1, *args, warmup=warm, iters=iters, reps=reps)))
             tf = fl / (t * 1e-3) / 1e12
             att = attainable_tflops(r["dtype"], r["M"], r["N"], r["K"], r["batch"], r["beta"])
             cells.append(dict(M=r["M"], N=r["N"], K=r["K"], batch=r["batch"], layout="NT"[r["tA"]] + "NT"[r["tB"]],
