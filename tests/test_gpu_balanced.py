@@ -177,6 +177,22 @@ def test_balanced_form_with_bias_and_bf16_output(gpu, ks):
         err = float(np.max(np.abs(C.cpu().numpy().astype(np.float64) - ref)))
         tol = tolerance(p) + 2.0 ** -22 * (float(np.max(np.abs(bias))) + float(np.max(np.abs(ref))))
         assert err <= tol, "kernel %d with bias: %.3e > %.3e" % (kid, err, tol)
+    # C kept in bf16: the second kernel rounds the summed value once, as the single-kernel epilogue does
+    C16 = wl.f32_to_bf16_rne(p.C0)
+    ref16 = C16.copy()
+    og.gemm_out_bf16(p.dtype, p.transA, p.transB, p.M, p.N, p.K, p.alpha, p.A, p.lda, p.B, p.ldb, p.beta, ref16,
+                     p.ldc, bias, p.batch, p.strideA, p.strideB, p.strideC)
+    reff = wl.bf16_to_f32(ref16).astype(np.float64)
+    for kid in balanced_ids(ks):
+        C = torch.from_numpy(C16.view(np.int16).copy()).cuda()
+        ks.gemm_out_bf16(ks.F32, kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb, p.beta, C,
+                         p.ldc, dbias, p.batch, p.strideA, p.strideB, p.strideC)
+        torch.cuda.synchronize()
+        got = C.cpu().numpy().view(np.uint16)
+        gotf = wl.bf16_to_f32(got).astype(np.float64)
+        bound = tolerance(p) + 2.0 ** -22 * 4.0 + 2.0 ** -7 * np.abs(reff)
+        assert np.all(np.isfinite(gotf)) and np.all(np.abs(gotf - reff) <= bound), "kernel %d, bf16 output" % kid
+        assert np.mean(got == ref16) > 0.97, "kernel %d, bf16 output: too few entries agree exactly" % kid
 
 
 @pytest.mark.parametrize("tA,tB", LAYOUTS)
