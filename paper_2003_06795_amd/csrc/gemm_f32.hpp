@@ -47,6 +47,18 @@ namespace ks {
 #define KS_F32_SK_MIN_WAVES(bm, bn, p1, p2) (((bm) / (p1)) * ((bn) / (p2)) >= 8 ? 4 : 3)
 #endif
 
+// Row padding of the row-contiguous operand's LDS tile in the balanced persistent form when the
+// other operand is K-contiguous and both are fetched as float4 (NN and TT layouts): the padding of
+// its partner instead of its own 4.  With unequal row lengths (130 and 132 floats at BK = 32) the
+// compiler keeps separate sets of fragment addresses for the two tiles, about 28 registers, which
+// the persistent form does not have (it spilled 13 - 14 of them and ran 16 % slower in NN than in
+// the other layouts); with equal ones it needs 110.  The tile is then written with 8-byte stores,
+// which cost the four-wave 64 x 64 member (168 registers to spend, no spills either way) 2 - 4 %:
+// eight-wave members only.  -1 = no override.
+constexpr int f32_pad_of_partner(bool sk, bool kc, bool partnerKc, bool vec, int bk, int threads) {
+    return sk && threads >= 512 && vec && !kc && partnerKc && bk <= 32 && (64 / bk) % 2 == 0 ? 64 / bk : -1;
+}
+
 enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3, CORE_KSLICE = 4 };
 
 template <int CORE, int BM, int BN, int P1, int P2>
@@ -60,7 +72,8 @@ struct F32Shape {
 // KC:  memory is [row][k] (k contiguous);  !KC: memory is [k][row] (row contiguous).
 // Units are float4 (VEC) or single floats walked so that consecutive lanes touch consecutive
 // addresses.  INNER = units along the contiguous direction, OUTER = the other direction.
-template <int ROWS, int BK, int NT, bool KC, bool VEC>
+// PAD >= 0 overrides the row padding chosen below (see f32_pad_of_partner).
+template <int ROWS, int BK, int NT, bool KC, bool VEC, int PAD = -1>
 struct TileLoader {
     static constexpr int W = VEC ? 4 : 1;
     static constexpr int INNER = (KC ? BK : ROWS) / W;
@@ -74,7 +87,8 @@ struct TileLoader {
     // keeps their 16-byte writes aligned.  (Measured: bank-conflict cycles of the 128 x 128 x 32
     // member fell to a third and the BK = 32 / 64 members gained 2 - 20 % on long K; giving the
     // lane groups of an MFMA read rows 4 or 8 apart instead of adjacent ones changed nothing.)
-    static constexpr int LDS_LD = ROWS + ((KC && VEC) ? (BK >= 64 ? 1 : 64 / BK) : 4);
+    static constexpr int LDS_LD = ROWS + (PAD >= 0 ? PAD : (KC && VEC) ? (BK >= 64 ? 1 : 64 / BK) : 4);
+    static_assert(!(VEC && !KC) || LDS_LD % 2 == 0, "row-contiguous vector writes need 8-byte alignment");
     static_assert((INNER <= NT && NT % INNER == 0) || (INNER > NT && INNER % NT == 0), "walk");
 
     float reg[ITERS][W];
@@ -119,9 +133,14 @@ struct TileLoader {
             if (UNITS % NT != 0 && outer >= OUTER) continue;
             const int r = KC ? outer : inner * W;
             const int k = KC ? inner * W : outer;
-            if constexpr (VEC && !KC) {
+            if constexpr (VEC && !KC && LDS_LD % 4 == 0) {
                 floatx4 v = {reg[it][0], reg[it][1], reg[it][2], reg[it][3]};
                 *reinterpret_cast<floatx4 *>(lds + k * LDS_LD + r) = v;
+            } else if constexpr (VEC && !KC) {
+                typedef float floatx2 __attribute__((ext_vector_type(2)));
+                floatx2 *dst = reinterpret_cast<floatx2 *>(lds + k * LDS_LD + r);
+                dst[0] = floatx2{reg[it][0], reg[it][1]};
+                dst[1] = floatx2{reg[it][2], reg[it][3]};
             } else if constexpr (VEC) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) lds[(k + j) * LDS_LD + r] = reg[it][j];
@@ -161,7 +180,8 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), (SK
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
     constexpr int NT = Shape::threads;                        // threads of one group
     static_assert(KW == 1 || CORE != CORE_FMA, "K groups need an MFMA core");
-    constexpr int LDA = TileLoader<BM, BK, NT, AKC, VEC>::LDS_LD, LDB = TileLoader<BN, BK, NT, BKC, VEC>::LDS_LD;
+    constexpr int PADA = f32_pad_of_partner(SK, AKC, BKC, VEC, BK, NT), PADB = f32_pad_of_partner(SK, BKC, AKC, VEC, BK, NT);
+    constexpr int LDA = TileLoader<BM, BK, NT, AKC, VEC, PADA>::LDS_LD, LDB = TileLoader<BN, BK, NT, BKC, VEC, PADB>::LDS_LD;
     __shared__ __attribute__((aligned(16))) float AsAll[KW][2][BK * LDA];
     __shared__ __attribute__((aligned(16))) float BsAll[KW][2][BK * LDB];
 
@@ -185,8 +205,8 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), (SK
     // K-steps in flight between global memory and LDS (each in its own set of staging registers):
     // small tiles are latency-bound - few waves per compute unit, short MFMA runs per K-step - and
     // afford several; large tiles hide the latency behind their MFMAs and keep the registers.
-    using LoaderA = TileLoader<BM, BK, NT, AKC, VEC>;
-    using LoaderB = TileLoader<BN, BK, NT, BKC, VEC>;
+    using LoaderA = TileLoader<BM, BK, NT, AKC, VEC, PADA>;
+    using LoaderB = TileLoader<BN, BK, NT, BKC, VEC, PADB>;
     constexpr int STAGE_REGS = (LoaderA::ITERS + LoaderB::ITERS) * LoaderA::W;
     constexpr int PF = KS_F32_PREFETCH(STAGE_REGS, NT);
     LoaderA la[PF];
