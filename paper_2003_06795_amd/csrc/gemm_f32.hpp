@@ -47,16 +47,23 @@ namespace ks {
 #define KS_F32_SK_MIN_WAVES(bm, bn, p1, p2) (((bm) / (p1)) * ((bn) / (p2)) >= 8 ? 4 : 3)
 #endif
 
-// Row padding of the row-contiguous operand's LDS tile in the balanced persistent form when the
-// other operand is K-contiguous and both are fetched as float4 (NN and TT layouts): the padding of
-// its partner instead of its own 4.  With unequal row lengths (130 and 132 floats at BK = 32) the
-// compiler keeps separate sets of fragment addresses for the two tiles, about 28 registers, which
-// the persistent form does not have (it spilled 13 - 14 of them and ran 16 % slower in NN than in
-// the other layouts); with equal ones it needs 110.  The tile is then written with 8-byte stores,
-// which cost the four-wave 64 x 64 member (168 registers to spend, no spills either way) 2 - 4 %:
-// eight-wave members only.  -1 = no override.
-constexpr int f32_pad_of_partner(bool sk, bool kc, bool partnerKc, bool vec, int bk, int threads) {
-    return sk && threads >= 512 && vec && !kc && partnerKc && bk <= 32 && (64 / bk) % 2 == 0 ? 64 / bk : -1;
+// Row padding of the row-contiguous operand's LDS tile when the other operand is K-contiguous and
+// both are fetched as float4 (NN and TT layouts): the padding of its partner instead of its own 4
+// for the members named below.  With unequal row lengths (130 and 132 floats at BK = 32) the
+// compiler keeps separate sets of fragment addresses for the two tiles, 23 - 28 registers.  The
+// balanced persistent form of the 128 x 128 x 32 member does not have them inside its budget of 128
+// (it spilled 13 - 14 and ran 16 % slower in NN than in NT / TN; with equal rows it needs 110), and
+// the sixteen-wave 64 x 64 x 32 member on 16 x 16 wave tiles loses its second resident work-group
+// (75 registers against 52).  The tile is then written with 8-byte stores, which costs elsewhere:
+// measured on the NN and TT rows of the tuning set, the three members on 16 x 16 wave tiles with
+// square tiles, K-step 32 and at least 512 threads gain 2.5 - 9 %, every other member is level or
+// loses 1 - 9 % (among them the four-wave 64 x 64 x 32 balanced member), so only those get it.
+// -1 = no override.
+constexpr int f32_pad_of_partner(bool sk, int core, int bm, int bn, int p1, int p2, int kw, bool kc, bool partnerKc,
+                                 bool vec, int bk, int threads) {
+    const bool balancedLarge = sk && threads >= 512;
+    const bool squareOn16 = core == 1 && bm == bn && p1 == 16 && p2 == 16 && bk == 32 && threads * kw >= 512;
+    return (balancedLarge || squareOn16) && vec && !kc && partnerKc && bk <= 32 && (64 / bk) % 2 == 0 ? 64 / bk : -1;
 }
 
 enum { CORE_FMA = 0, CORE_MFMA16 = 1, CORE_MFMA32 = 2, CORE_DIRECT = 3, CORE_KSLICE = 4 };
@@ -180,7 +187,8 @@ __global__ __launch_bounds__((F32Shape<CORE, BM, BN, P1, P2>::threads * KW), (SK
     using Shape = F32Shape<CORE, BM, BN, P1, P2>;
     constexpr int NT = Shape::threads;                        // threads of one group
     static_assert(KW == 1 || CORE != CORE_FMA, "K groups need an MFMA core");
-    constexpr int PADA = f32_pad_of_partner(SK, AKC, BKC, VEC, BK, NT), PADB = f32_pad_of_partner(SK, BKC, AKC, VEC, BK, NT);
+    constexpr int PADA = f32_pad_of_partner(SK, CORE, BM, BN, P1, P2, KW, AKC, BKC, VEC, BK, NT);
+    constexpr int PADB = f32_pad_of_partner(SK, CORE, BM, BN, P1, P2, KW, BKC, AKC, VEC, BK, NT);
     constexpr int LDA = TileLoader<BM, BK, NT, AKC, VEC, PADA>::LDS_LD, LDB = TileLoader<BN, BK, NT, BKC, VEC, PADB>::LDS_LD;
     __shared__ __attribute__((aligned(16))) float AsAll[KW][2][BK * LDA];
     __shared__ __attribute__((aligned(16))) float BsAll[KW][2][BK * LDB];
