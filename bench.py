@@ -290,7 +290,8 @@ def time_set(ks, torch, workload, iters=10):
             tf = fl / (t * 1e-3) / 1e12
             att = attainable_tflops(r["dtype"], r["M"], r["N"], r["K"], r["batch"], r["beta"])
             cells.append(dict(M=r["M"], N=r["N"], K=r["K"], batch=r["batch"], layout="NT"[r["tA"]] + "NT"[r["tB"]],
-                              kernel=plan["kernel_id"], split_k=plan["split_k"], ms=t, tflops=tf,
+                              kernel=plan["kernel_id"], split_k=plan["split_k"], tail_split=plan["tail_split"], ms=t,
+                              tflops=tf,
                               frac_of_peak=tf / PEAK[r["dtype"]], attainable_tflops=att, frac_of_attainable=tf / att))
         del bufs
         torch.cuda.empty_cache()
@@ -466,7 +467,8 @@ def main():
     esz = 4 if dtype == "f32" else 2
     for i, s in enumerate(sym):
         d = by.setdefault(s, dict(pass_time=0.0, pass_flops=0.0, pass_bytes=0.0, rows=0, all_time=0.0,
-                                  all_launches=0, split=plans[i]["split_k"] > 1, divided=0))
+                                  all_launches=0, split=plans[i]["split_k"] > 1 or plans[i]["tail_split"] > 0,
+                                  divided=0))
         d["divided"] += int(plans[i]["divided_tiles"] > 0)
         r = rows[i]
         d["pass_time"] += float(med[i]) * 1e-3
@@ -513,6 +515,7 @@ def main():
                                               "per row"}[a.workload],
                    "rows": len(rows), "kernels_used": len(set(chosen)),
                    "rows_that_split_k": int(sum(p["split_k"] > 1 for p in plans)),
+                   "rows_with_a_split_last_round": int(sum(p["tail_split"] > 0 for p in plans)),
                    "rows_in_balanced_form": int(sum(p["balanced_groups"] > 0 for p in plans)),
                    "launches_per_step": int(sum(1 + SAMPLES * r for r in reps)),
                    "timing": ("per row and step: ks_time_gemm with 1 untimed launch and %d samples of `reps` back-to-back "

@@ -33,8 +33,8 @@
  *     that both run a split-K member must not be in flight together (same
  *     stream, or ordered by the caller); ks_gemm_with_workspace takes the
  *     scratch per call and has no such limit.  ks_set_workspace,
- *     ks_set_fast_path, ks_set_tiles_per_workgroup, ks_set_balanced_groups and
- *     ks_set_selector are not thread-safe: they change process-wide settings
+ *     ks_set_fast_path, ks_set_tiles_per_workgroup, ks_set_balanced_groups,
+ *     ks_set_tail_split and ks_set_selector are not thread-safe: they change process-wide settings
  *     that the compute entry points read.  ks_time_gemm keeps its events per
  *     host thread.  The library acts on the calling thread's current HIP device
  *     and never changes it.
@@ -240,6 +240,10 @@ typedef struct {
     int64_t workgroups;
     int32_t balanced_groups;      /* > 0: the balanced persistent form runs, with this many work-groups */
     int32_t divided_tiles;        /* left-over tiles of that form, handed to its second kernel (0: none launched) */
+    int32_t tail_split;           /* > 0: hybrid launch of a 16-bit member (ks_set_tail_split): the tiles of the
+                                     last, partly filled round of work-groups run in this many K partitions
+                                     (three kernels: whole tiles, partitioned tiles, their reduction) */
+    int32_t reserved_;            /* 0 */
 } ks_launch_plan_t;
 int ks_gemm_plan(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
                  float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
@@ -307,6 +311,19 @@ int ks_set_tiles_per_workgroup(int n);
  * follows the forced count.  Results stay within the stated bound but the summation order of
  * divided tiles changes with the count.  Not thread-safe. */
 int ks_set_balanced_groups(int per_cu);
+
+/* Hybrid launches of the 16-bit members whose K split is chosen per call (split_k == 0), on their
+ * direct-to-LDS path with batch 1 (the launch shape is the run-time axis of the Section II kernel).
+ * Members whose LDS stages admit one work-group per compute unit take part (a round is then 256
+ * work-groups).  When the tiles fill at least one whole round and leave a partly filled last round, the tiles of that round are cut along K into as many partitions as fill it (2 to
+ * 16, at least two K-steps each): whole tiles, the partitioned tiles (partial sums as compact
+ * tiles in the workspace, at most work-groups-per-round tiles of bm x bn floats) and a reduction
+ * that adds the partitions in order run as three kernels on the stream.  partitions == -1 (the
+ * default) takes the form where a cost estimate in K-steps says it saves 3 % of the call and the
+ * workspace holds the tiles; 0 never; 2 .. 16 forces it wherever it can run, with at most that
+ * many partitions (testing and tuning).  Results stay within the stated bound (the summation order
+ * of the partitioned tiles changes).  Not thread-safe. */
+int ks_set_tail_split(int partitions);
 
 /* Measurement aid: copies `bytes` (a multiple of 16; both device pointers 16-byte aligned) with a
  * plain one-read-one-write kernel (ks::copy_kernel).  Hardware traffic counters collected over a

@@ -96,6 +96,7 @@ void init_tables() {
 int g_forceGeneric = 0;
 int g_tilesPerWG = 0;        // 0: chosen per call (multi_tiles); n >= 1: forced
 int g_skPerCU = 0;           // 0: the member's own count of work-groups per compute unit; n >= 1: forced
+int g_tailSplit = -1;        // -1: chosen per call (tail_split); 0: never; n >= 2: forced where it can run
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
@@ -136,6 +137,44 @@ int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles, bool f3
         if (bestCost < 0 || cost < bestCost) { bestCost = cost; best = s; }
     }
     return best;
+}
+
+// K partitions for the last, partly filled round of work-groups of a 16-bit member whose split is
+// chosen per call (0 = launch every tile whole).  With `slots` work-groups resident at once, T
+// tiles take ceil(T / slots) rounds although the last one may hold only a few tiles; cutting the
+// K range of just those left-over tiles into s = slots / left-over partitions fills that round
+// with work-groups that are s times shorter.  Same cost units as auto_split; the partitioned round
+// also pays its tiles of partial sums and a third launch.  Only with at least one whole round
+// before it (otherwise auto_split decides), and only when it saves 3 % of the call.
+bool tail_split_member(const InstanceDesc *d) {
+    // members whose LDS stages leave room for one work-group per compute unit: their round is 256
+    // work-groups for certain (smaller members share a unit and suffer less from a short last round)
+    return d->splitK == 0 && d->ldsBytes > 0 && (160 * 1024) / d->ldsBytes == 1;
+}
+// scratch of the largest partitioning tail_split can choose for this many tiles (0: no hybrid launch)
+size_t tail_split_bytes(const InstanceDesc *d, int64_t tiles) {
+    if (!tail_split_member(d)) return 0;
+    const int64_t slots = split_slots(d, false);
+    const int64_t tail = tiles % slots;
+    if (tiles < slots || tail == 0) return 0;
+    int64_t s = slots / tail;
+    if (s > 16) s = 16;
+    return s >= 2 ? (size_t)s * (size_t)tail * (size_t)d->bm * (size_t)d->bn * sizeof(float) : 0;
+}
+int64_t tail_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles) {
+    if (!tail_split_member(d)) return 0;
+    const int64_t slots = split_slots(d, false);
+    const int64_t rounds = tiles / slots, tail = tiles % slots;
+    if (rounds == 0 || tail == 0) return 0;
+    int64_t s = slots / tail;
+    if (s > 16) s = 16;
+    if (2 * s > kTiles) s = kTiles / 2;
+    if (g_tailSplit >= 2) return s >= 2 ? (s < g_tailSplit ? s : g_tailSplit) : 0;
+    if (s < 2) return 0;
+    const int64_t partial = (4LL * d->bm * d->bn) / ((int64_t)(d->bm + d->bn) * d->bk);
+    const int64_t plain = (rounds + 1) * (kTiles + 6);
+    const int64_t hybrid = rounds * (kTiles + 6) + (kTiles + s - 1) / s + 6 + partial + 14;
+    return 100 * hybrid <= 97 * plain ? s : 0;
 }
 
 // Tiles one work-group of a multi-tile fp32 member walks.  Walking T tiles takes the work-group
@@ -258,6 +297,53 @@ __global__ void splitk_reduce_kernel(const float *ws, float *C, long long ldc, l
     }
 }
 
+// Second pass of a launch whose last round was partitioned along K (tail_split): work-group
+// (b, y) adds up rows 8 y .. 8 y + 7 of the compact partial tiles [partition][b] of tile
+// tileBase + b in partition order and writes them to C.  Few tiles are partitioned (fewer than one
+// round of work-groups), so the rows of a tile are spread over many work-groups; partial sums are
+// read 16 bytes per lane (the workspace is 16-byte aligned, tiles are multiples of 16 floats wide).
+#define KS_TAIL_REDUCE_ROWS 8
+__global__ void tail_reduce_kernel(const GemmParams p) {
+    const TileCoord tc = tile_of_logical(p, blockIdx.x);       // partition 0 of tile tileBase + blockIdx.x
+    const int bm = p.bm, bn = p.bn, S = p.splitK;
+    const long long tileElems = (long long)bm * bn;
+    const float *w0 = p.ws + (long long)blockIdx.x * tileElems;
+    const long long per = (long long)p.tileSpan * tileElems;
+    const int r0 = tc.tm * bm, c0 = tc.tn * bn;
+    const int rows = p.M - r0 < bm ? p.M - r0 : bm, cols = p.N - c0 < bn ? p.N - c0 : bn;
+    const int rFirst = (int)blockIdx.y * KS_TAIL_REDUCE_ROWS;
+    const int q = bn / 4;                                      // float4 units per tile row
+    for (int u = threadIdx.x; u < KS_TAIL_REDUCE_ROWS * q; u += blockDim.x) {
+        const int r = rFirst + u / q, c = (u % q) * 4;
+        if (r >= rows || c >= cols) continue;
+        const float *w = w0 + (long long)r * bn + c;
+        floatx4 acc = *reinterpret_cast<const floatx4 *>(w);
+        int s = 1;
+        for (; s + 8 <= S; s += 8) {                 // eight independent loads, added in partition order
+            floatx4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const floatx4 *>(w + (long long)(s + k) * per);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc += v[k];
+        }
+        for (; s < S; ++s) acc += *reinterpret_cast<const floatx4 *>(w + (long long)s * per);
+        const long long at = (long long)(r0 + r) * p.ldc + (c0 + c);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (c + e >= cols) break;
+            if (p.out16) {
+                store_bf16_out(p.C, at + e, acc[e], p.alpha, p.beta, p.bias ? p.bias[c0 + c + e] : 0.0f);
+                continue;
+            }
+            float *cp = p.C + at + e;
+            float v = p.alpha * acc[e];
+            if (p.beta != 0.0f) v = fmaf(p.beta, *cp, v);
+            if (p.bias) v += p.bias[c0 + c + e];
+            *cp = v;
+        }
+    }
+}
+
 int validate(int transA, int transB, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
              const void *B, int64_t ldb, const float *C, int64_t ldc, int64_t batch,
              int64_t strideC) {
@@ -361,6 +447,7 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
     p.tilesPerWG = 1;
     p.bandRows = d->band;
     p.skGroups = 0; p.skRounds = 0; p.skTailTiles = 0;
+    p.tileBase = 0; p.tileSpan = 0; p.bm = d->bm; p.bn = d->bn;
     if (d->sk > 0) {
         // Balanced persistent form where it pays (measured against the plain member of the same
         // tiles on the tuning tables): tiles that do not divide evenly over the work-groups, fewer
@@ -409,20 +496,53 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
     const int f16Bit = dtype == KS_F16 ? 16 : 0;     // same 16-bit members, binary16 MFMA
     const bool dma = dtype != KS_F32 && vec && g_forceGeneric == 0 && K % d->bk == 0 &&
                      lda <= (1LL << 22) && ldb <= (1LL << 22);
+    // Hybrid launch of a 16-bit member whose split is chosen per call: whole rounds of work-groups
+    // compute their tiles over all of K, the tiles of the last, partly filled round are cut along
+    // K (tail_split), and a third kernel adds their partial tiles up.
+    int64_t tailS = 0, tailTiles = 0, mainGrid = grid64;
+    if (dma && d->splitK == 0 && p.splitK == 1 && batch == 1 && g_tailSplit != 0 && wsp.ptr &&
+        aligned(wsp.ptr, 16)) {
+        const int64_t slots = split_slots(d, false);
+        const int64_t s = tail_split(d, grid64, kTiles);
+        const int64_t tail = grid64 % slots;
+        if (s >= 2 && (size_t)s * (size_t)tail * (size_t)d->bm * (size_t)d->bn * sizeof(float) <= wsp.bytes) {
+            tailS = s; tailTiles = tail; mainGrid = grid64 - tail;
+            p.grid3d = 0;                            // both launches walk the one-dimensional tile order
+        }
+    }
     if (planOnly) {
+        planOnly->tail_split = (int32_t)tailS;
         planOnly->split_k = p.splitK;
         planOnly->vector_loads = vec ? 1 : 0;
         planOnly->grid_3d = p.grid3d;
         planOnly->tiles_per_workgroup = p.tilesPerWG;
-        planOnly->workgroups = grid64;
+        planOnly->workgroups = tailS ? mainGrid + tailTiles * tailS : grid64;
         planOnly->balanced_groups = p.skGroups;
         planOnly->divided_tiles = p.skTailTiles;
+        planOnly->reserved_ = 0;
         planOnly->path = !dma ? 0
                          : bf16_two_groups(d->core == KS_CORE_MFMA32 ? 32 : 16, d->bm, d->bn, d->bk, d->p1, d->p2,
                                            d->ldsBytes / (d->bk * (d->bm + d->bn) * 2))
                              ? 2
                              : 1;
         return KS_OK;
+    }
+    if (tailS) {
+        const int layoutBits = (akc ? 2 : 0) + (bkc ? 1 : 0) + f16Bit;
+        g_bf16_dma[id](p, (int)mainGrid, layoutBits, stream);
+        if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
+        GemmParams q = p;
+        q.splitK = (int)tailS;
+        q.kChunk = (int)(((kTiles + tailS - 1) / tailS) * d->bk);
+        q.tileBase = (int)mainGrid;
+        q.tileSpan = (int)tailTiles;
+        q.ws = static_cast<float *>(wsp.ptr);
+        g_bf16_dma[id](q, (int)(tailTiles * tailS), layoutBits + 8, stream);
+        if (hipGetLastError() != hipSuccess) return KS_ERR_LAUNCH;
+        hipLaunchKernelGGL(tail_reduce_kernel,
+                           dim3((unsigned)tailTiles, (unsigned)((d->bm + KS_TAIL_REDUCE_ROWS - 1) / KS_TAIL_REDUCE_ROWS)),
+                           dim3(256), 0, stream, q);
+        return hipGetLastError() == hipSuccess ? KS_OK : KS_ERR_LAUNCH;
     }
     if (dma)
         g_bf16_dma[id](p, (int)grid64, (akc ? 2 : 0) + (bkc ? 1 : 0) + splitBit + f16Bit, stream);
@@ -524,6 +644,12 @@ extern "C" int ks_set_balanced_groups(int per_cu) {
     return KS_OK;
 }
 
+extern "C" int ks_set_tail_split(int partitions) {
+    if (partitions != -1 && partitions != 0 && (partitions < 2 || partitions > 16)) return KS_ERR_INVALID_ARG;
+    g_tailSplit = partitions;
+    return KS_OK;
+}
+
 extern "C" int ks_set_workspace(void *device_ptr, size_t bytes) {
     if (device_ptr == nullptr || bytes == 0) {
         g_ws = nullptr;
@@ -544,8 +670,9 @@ extern "C" size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M,
     if (d->splitK == 1) return 0;
     int64_t s = d->splitK;
     if (s == 0) {
-        s = auto_split_max(d, ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch, dtype == KS_F32);
-        if (s <= 1) return 0;
+        const int64_t tiles = ((M + d->bm - 1) / d->bm) * ((N + d->bn - 1) / d->bn) * batch;
+        s = auto_split_max(d, tiles, dtype == KS_F32);
+        if (s <= 1) return dtype != KS_F32 && batch == 1 ? tail_split_bytes(d, tiles) : 0;
     }
     return (size_t)s * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
 }

@@ -33,6 +33,11 @@ struct GemmParams {
     // skGroups work-groups; each computes skRounds whole tiles (logical tiles round * skGroups + its
     // own logical id) and then an equal share of the K-steps of the skTailTiles tiles that are left
     int skGroups, skRounds, skTailTiles;
+    // a launch over part of the tiles (the split tail of a hybrid launch, see dispatch.hip): logical
+    // ids 0 .. tileSpan * splitK - 1 stand for the tiles tileBase .. tileBase + tileSpan - 1 of the
+    // one-dimensional order, partition-major, and partial sums go to the workspace as compact
+    // bm x bn tiles [partition][tile - tileBase].  tileSpan == 0 everywhere else.
+    int tileBase, tileSpan, bm, bn;
 };
 
 // K-steps [first, last) of the left-over tiles (flattened as tile * steps-per-tile + step) that
@@ -104,8 +109,8 @@ __device__ __forceinline__ unsigned logical_of_block() {
 // tile with logical id `logical` of a one-dimensional launch: units (batch item, K partition) in
 // order, inside a unit bands of p.bandRows tile-rows walked column-major
 __device__ __forceinline__ TileCoord tile_of_logical(const GemmParams &p, unsigned logical) {
-    const unsigned per = (unsigned)p.tilesM * (unsigned)p.tilesN;
-    const unsigned unit = logical / per, t = logical - unit * per;
+    const unsigned per = p.tileSpan ? (unsigned)p.tileSpan : (unsigned)p.tilesM * (unsigned)p.tilesN;
+    const unsigned unit = logical / per, t = logical - unit * per + (unsigned)p.tileBase;
     TileCoord c;
     c.batch = (int)(unit / (unsigned)p.splitK);
     c.split = (int)(unit - (unsigned)c.batch * (unsigned)p.splitK);
@@ -117,6 +122,30 @@ __device__ __forceinline__ TileCoord tile_of_logical(const GemmParams &p, unsign
     c.tn = (int)(in / rows);
     c.tm = (int)(first + (in - (unsigned)c.tn * rows));
     return c;
+}
+
+// inverse of the tile walk above: position of tile (tm, tn) in the one-dimensional order of a unit
+__device__ __forceinline__ unsigned logical_of_tile(const GemmParams &p, int tm, int tn) {
+    const unsigned h = (unsigned)p.bandRows;
+    const unsigned g = (unsigned)tm / h, first = g * h;
+    const unsigned rows = ((unsigned)p.tilesM - first) < h ? ((unsigned)p.tilesM - first) : h;
+    return g * h * (unsigned)p.tilesN + (unsigned)tn * rows + ((unsigned)tm - first);
+}
+
+// Where a split-K instantiation puts its partial sums and with which row length: the dense
+// [partition][batch][M][N] array, or, in a launch over part of the tiles, the compact tile
+// [partition][tile - tileBase] (the returned base is shifted so that base + row * ld + col with
+// the absolute row and column lands inside that tile).
+__device__ __forceinline__ float *partial_base(const GemmParams &p, const TileCoord &tc, long long &ld) {
+    if (p.tileSpan) {
+        ld = p.bn;
+        const long long tileElems = (long long)p.bm * p.bn;
+        const long long rel = (long long)logical_of_tile(p, tc.tm, tc.tn) - p.tileBase;
+        return p.ws + ((long long)tc.split * p.tileSpan + rel) * tileElems -
+               ((long long)tc.tm * p.bm * p.bn + (long long)tc.tn * p.bn);
+    }
+    ld = p.N;
+    return p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)p.M * p.N;
 }
 
 __device__ __forceinline__ TileCoord tile_of_block(const GemmParams &p) {
@@ -149,9 +178,10 @@ __device__ __forceinline__ void write_tile(const GemmParams &p, const TileCoord 
                                            Visit visit) {
     const int M = p.M, N = p.N;
     if constexpr (SPLIT) {
-        float *w = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)M * N;
+        long long wld;
+        float *w = partial_base(p, tc, wld);
         visit([&](int row, int col, float acc) {
-            if (row < M && col < N) w[(long long)row * N + col] = acc;
+            if (row < M && col < N) w[(long long)row * wld + col] = acc;
         });
     } else if (p.out16) {
         const float alpha = p.alpha, beta = p.beta;
@@ -209,8 +239,8 @@ __device__ __forceinline__ OutTarget out_target(const GemmParams &p, const TileC
     OutTarget o;
     o.M = p.M; o.N = p.N;
     if constexpr (SPLIT) {
-        o.base = p.ws + ((long long)tc.split * p.batch + tc.batch) * (long long)p.M * p.N;
-        o.ld = p.N; o.alpha = 1.0f; o.beta = 0.0f; o.bias = nullptr; o.out16 = 0; o.off16 = 0;
+        o.base = partial_base(p, tc, o.ld);
+        o.alpha = 1.0f; o.beta = 0.0f; o.bias = nullptr; o.out16 = 0; o.off16 = 0;
     } else {
         o.base = Cb; o.ld = p.ldc; o.alpha = p.alpha; o.beta = p.beta; o.bias = p.bias; o.out16 = p.out16;
         o.off16 = (long long)tc.batch * p.strideC16;
