@@ -182,3 +182,37 @@ def test_rule_switch_and_workspace_fall_back(gpu):
     bb, ii, jj = gpu.sample_entries(p, 4000, 3)
     err = float(np.max(np.abs(got[ii * p.ldc + jj].astype(np.float64) - gpu.oracle_entries(p, bb, ii, jj))))
     assert err <= tolerance(p)
+
+
+def test_scratch_passed_per_call_and_static_scratch(gpu):
+    """The partial tiles may also live in a workspace handed over per call or in the library's static
+    array (when it is large enough); the registered workspace is then not touched."""
+    import torch
+    import paper_2003_06795_amd.binding as ks
+    kid = [i for i in per_call_members(ks) if ks.kernel_info(ks.BF16, i)["bm"] == 128][-1]
+    ki = ks.kernel_info(ks.BF16, kid)
+    M, N, K = shape_with_a_tail(ki, extra=5, K=1024)
+    p = wl.make_problem("bf16", 0, 1, M, N, K, alpha=1.0, beta=0.5, seed=74, key=0, dist="normal")
+    dp = gpu.DeviceProblem(p)
+    try:
+        ks.set_tail_split(4)
+        assert plan_of(ks, gpu, p, dp, kid)["tail_split"] >= 2
+        ref = dp.run(kid)                                   # registered workspace
+        need = ks.workspace_bytes_needed(ks.BF16, kid, M, N, 1)
+        assert need > 0
+        canary = torch.full((gpu.ensure_workspace(1).numel(),), 3.5, dtype=torch.float32, device="cuda")
+        ks.set_workspace(canary)
+        own = torch.empty(need // 4, dtype=torch.float32, device="cuda")
+        C = dp.C0.clone()
+        ks.gemm_with_workspace(ks.BF16, kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb,
+                               p.beta, C, p.ldc, own, batch=1)
+        D = dp.C0.clone()
+        ks.gemm_static_scratch(ks.BF16, kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb,
+                               p.beta, D, p.ldc)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), ref)
+        assert np.array_equal(D.cpu().numpy(), ref)
+        assert bool((canary == 3.5).all())
+    finally:
+        ks.set_tail_split(-1)
+        ks.set_workspace(gpu.ensure_workspace(1))
