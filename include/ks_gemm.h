@@ -370,7 +370,10 @@ int ks_bf16_ablation(int mode, const uint16_t *A_device, const uint16_t *B_devic
  * buffer per process (at least 4-byte aligned; 16-byte alignment lets the reduction pass use
  * 16-byte accesses); NULL / 0 unregisters.  Kernels with split_k == 1 never touch it. */
 int ks_set_workspace(void *device_ptr, size_t bytes);
-/* Bytes the kernel would like for this output size (for split_k == 0 the most it can use). */
+/* Bytes the kernel would like for this output size (for split_k == 0 the most it can use: the
+ * partial sums of the largest partition count it may choose, or, for a 16-bit member that launches
+ * in the hybrid form on this many tiles, the compact partial tiles of at most 16 partitions of its
+ * last round; for a member with a balanced persistent form, the raw tiles of its work-groups). */
 size_t ks_workspace_bytes_needed(int dtype, int kernel_id, int64_t M, int64_t N, int64_t batch);
 
 /* ---------------------------------------------------------------- offline tuner (host only)
