@@ -469,7 +469,8 @@ def main():
         # a row that runs more than one kernel inside its timed interval (split-K and its reduction,
         # a balanced launch that divides tiles and its second kernel, a hybrid launch) is booked
         # under a name of its own: its interval is not one kernel's duration
-        multi = plans[i]["split_k"] > 1 or plans[i]["tail_split"] > 0 or plans[i]["divided_tiles"] > 0
+        multi = (plans[i]["split_k"] > 1 or plans[i]["tail_split"] > 0 or plans[i]["divided_tiles"] > 0 or
+                 plans[i]["k_remainder"] > 0)
         d = by.setdefault(s + (" + further kernels" if multi else ""),
                           dict(pass_time=0.0, pass_flops=0.0, pass_bytes=0.0, rows=0, all_time=0.0, all_launches=0,
                                split=multi))

@@ -243,7 +243,10 @@ typedef struct {
     int32_t tail_split;           /* > 0: hybrid launch of a 16-bit member (ks_set_tail_split): the tiles of the
                                      last, partly filled round of work-groups run in this many K partitions
                                      (three kernels: whole tiles, partitioned tiles, their reduction) */
-    int32_t reserved_;            /* 0 */
+    int32_t k_remainder;          /* > 0 (16-bit operands only): K is not a whole number of the member's K-steps;
+                                     the last k_remainder of K run first through the member's general kernel
+                                     (applying alpha, beta and the bias), then the whole K-steps run on the
+                                     direct-to-LDS path with beta = 1, which the other fields describe */
 } ks_launch_plan_t;
 int ks_gemm_plan(int dtype, int kernel_id, int transA, int transB, int64_t M, int64_t N, int64_t K,
                  float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
@@ -289,8 +292,13 @@ int ks_get_selector(int dtype, ks_tree_node_t *nodes, int cap);
 
 /* The bf16 instantiations have two code paths with the same tiles: a generic one (any alignment,
  * any K) and a direct-to-LDS one used when operands are 16-byte aligned, leading dimensions and
- * contiguous extents are multiples of 8 and K is a multiple of the K-step.  enabled == 0 forces
- * the generic path (for testing it at aligned shapes); nonzero restores the default. */
+ * contiguous extents are multiples of 8 and K is a multiple of the K-step.  When only the last
+ * condition fails (K a multiple of 8 and at least four K-steps, output in fp32; with both operands
+ * K-contiguous, where the generic path is at its best, only for outputs of 2^24 entries or more), the call runs as
+ * two launches: the remainder of K beyond the whole K-steps through the generic path first, with
+ * alpha, beta and the bias, then the whole K-steps through the direct-to-LDS path with beta = 1
+ * (ks_launch_plan_t::k_remainder).  enabled == 0 forces the generic path for all of K (for testing
+ * it at aligned shapes); nonzero restores the default. */
 int ks_set_fast_path(int enabled);
 
 /* The large-tile fp32 32x32-MFMA members (LDS-staged, tile of at least 8192 entries and 128

@@ -36,7 +36,7 @@ class LaunchPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("kernel_id", "split_k", "path", "vector_loads", "grid_3d", "tiles_per_workgroup")] + \
                [("workgroups", ctypes.c_int64), ("balanced_groups", ctypes.c_int32), ("divided_tiles", ctypes.c_int32),
-                ("tail_split", ctypes.c_int32), ("reserved_", ctypes.c_int32)]
+                ("tail_split", ctypes.c_int32), ("k_remainder", ctypes.c_int32)]
 
 
 class TreeNode(ctypes.Structure):

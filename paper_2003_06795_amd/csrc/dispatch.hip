@@ -380,6 +380,8 @@ struct Workspace {
 };
 Workspace registered_ws() { return Workspace{g_ws, g_wsBytes}; }
 
+int remainder_member(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int tA, int tB, Workspace w);
+
 int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
            const void *A, int64_t lda, const void *B, int64_t ldb, float beta, float *C, int64_t ldc,
            int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, hipStream_t stream,
@@ -411,6 +413,45 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
 
     // a pruned build holds only the kept members
     if ((dtype == KS_F32 ? g_f32[id] : g_bf16[id]) == nullptr) return KS_ERR_UNSUPPORTED;
+
+    // 16-bit operands whose K is not a whole number of K-steps would take the member's general
+    // kernel for all of K (measured 1.5 - 2.2 times slower than the direct-to-LDS path on large
+    // problems).  Where everything else qualifies for that path, the K range is cut instead: the
+    // remainder (fewer than one K-step, general kernel) goes first and applies alpha, beta and the
+    // bias, then the whole K-steps run on the fast path with beta = 1.  The partial result passes
+    // through C in fp32 (one more rounding per entry, far inside the bound), so an output kept in
+    // bf16 is not served this way.  The two extra passes over C cost 15 - 40 us on 2048^2 .. 4096^2
+    // outputs; measured against the general kernel over all of K the cut gains 24 - 100 % when an
+    // operand is not K-contiguous (NN, TN, TT; level at 2048^2 NN), while with both operands
+    // K-contiguous (NT), where the general kernel is at its best, it loses 40 % at 2048^2, is level
+    // at 1024^2 and gains 4 - 12 % from 4096^2 on: NT is cut only for outputs of at least 2^24 entries.
+    if (dtype != KS_F32 && !out16 && g_forceGeneric == 0 && K % d->bk != 0 && K % 8 == 0 && K >= 4LL * d->bk) {
+        const int64_t Kr = K % d->bk, Kh = K - Kr;
+        const bool akc = transA == 0, bkc = transB == 1;
+        const bool pays = !(akc && bkc) || M * N >= (1LL << 24);
+        const bool vecOk = pays && aligned(A, 16) && aligned(B, 16) && lda % 8 == 0 && ldb % 8 == 0 && (akc || M % 8 == 0) &&
+                           (bkc || N % 8 == 0) && (batch == 1 || (strideA % 8 == 0 && strideB % 8 == 0)) &&
+                           lda <= (1LL << 22) && ldb <= (1LL << 22);
+        if (vecOk) {
+            const uint16_t *Ar = static_cast<const uint16_t *>(A) + (akc ? Kh : Kh * lda);
+            const uint16_t *Br = static_cast<const uint16_t *>(B) + (bkc ? Kh : Kh * ldb);
+            if (planOnly) {
+                const int prc = run_ws(wsp, dtype, id, transA, transB, M, N, Kh, alpha, A, lda, B, ldb, 1.0f, C, ldc, batch,
+                                       strideA, strideB, strideC, stream, nullptr, 0, planOnly);
+                if (prc == KS_OK) planOnly->k_remainder = (int32_t)Kr;
+                return prc;
+            }
+            // the remainder is a GEMM with a very short K of its own, bound by the pass over C: it
+            // runs with the member the deployed tree names for that problem
+            int idr = remainder_member(dtype, M, N, Kr, batch, transA, transB, wsp);
+            if (idr < 0) idr = id;
+            const int r1 = run_ws(wsp, dtype, idr, transA, transB, M, N, Kr, alpha, Ar, lda, Br, ldb, beta, C, ldc, batch,
+                                  strideA, strideB, strideC, stream, bias, 0, nullptr);
+            if (r1 != KS_OK) return r1;
+            return run_ws(wsp, dtype, id, transA, transB, M, N, Kh, alpha, A, lda, B, ldb, 1.0f, C, ldc, batch, strideA,
+                          strideB, strideC, stream, nullptr, 0, nullptr);
+        }
+    }
 
     GemmParams p;
     p.A = A; p.B = B; p.C = C; p.ws = nullptr; p.bias = bias; p.out16 = out16;
@@ -519,7 +560,6 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
         planOnly->workgroups = tailS ? mainGrid + tailTiles * tailS : grid64;
         planOnly->balanced_groups = p.skGroups;
         planOnly->divided_tiles = p.skTailTiles;
-        planOnly->reserved_ = 0;
         planOnly->path = !dma ? 0
                          : bf16_two_groups(d->core == KS_CORE_MFMA32 ? 32 : 16, d->bm, d->bn, d->bk, d->p1, d->p2,
                                            d->ldsBytes / (d->bk * (d->bm + d->bn) * 2))
@@ -704,6 +744,18 @@ static int select_checked(int dtype, int64_t M, int64_t N, int64_t K, int64_t ba
         }
     return id;
 }
+
+namespace ks {
+namespace {
+// member that runs the remainder of a K range that is not a whole number of K-steps (run_ws)
+int remainder_member(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch, int tA, int tB, Workspace w) {
+    const int id = select_checked(dtype, M, N, K, batch, tA, tB, w);
+    if (id < 0) return id;
+    std::call_once(g_once, init_tables);
+    return g_bf16[id] != nullptr ? id : -1;
+}
+}  // namespace
+}  // namespace ks
 
 extern "C" int ks_gemm_f32_with_kernel(int kernel_id, int transA, int transB, int64_t M, int64_t N,
                                        int64_t K, float alpha, const float *A, int64_t lda,
