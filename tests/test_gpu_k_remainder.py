@@ -108,3 +108,23 @@ def test_bias_fp16_and_the_cases_that_are_not_cut(gpu):
     gotf = wl.bf16_to_f32(D.cpu().numpy().view(np.uint16)).astype(np.float64)
     reff = wl.bf16_to_f32(ref16).astype(np.float64)
     assert np.all(np.abs(gotf - reff) <= tolerance(p) + 2.0 ** -7 * np.abs(reff))
+
+
+def test_cut_k_together_with_a_hybrid_launch(gpu):
+    """The whole K-steps of a cut call may themselves launch in the hybrid form (partly filled last
+    round partitioned along K): four kernels in a row on one output."""
+    import paper_2003_06795_amd.binding as ks
+    ks.set_fast_path(True)
+    ks.set_tail_split(-1)
+    big = [i for i in range(ks.num_kernels(ks.BF16)) if ks.kernel_info(ks.BF16, i)["split_k"] == 0 and
+           ks.kernel_info(ks.BF16, i)["bm"] == 256 and ks.kernel_info(ks.BF16, i)["bn"] == 256 and
+           ks.kernel_info(ks.BF16, i)["threads"] == 512][-1]
+    M, N, K = 17 * 256 - 8, 17 * 256 - 24, 2048 + 24
+    p = wl.make_problem("bf16", 0, 0, M, N, K, alpha=1.0, beta=0.5, seed=83, key=0, dist="normal")
+    dp = gpu.DeviceProblem(p)
+    plan = plan_of(ks, gpu, p, dp, big)
+    assert plan["k_remainder"] == 24 and plan["tail_split"] >= 2, plan
+    got = dp.run(big)
+    bb, ii, jj = gpu.sample_entries(p, 4000, 9)
+    err = float(np.max(np.abs(got[ii * p.ldc + jj].astype(np.float64) - gpu.oracle_entries(p, bb, ii, jj))))
+    assert err <= tolerance(p)
