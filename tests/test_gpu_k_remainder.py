@@ -128,3 +128,34 @@ def test_cut_k_together_with_a_hybrid_launch(gpu):
     bb, ii, jj = gpu.sample_entries(p, 4000, 9)
     err = float(np.max(np.abs(got[ii * p.ldc + jj].astype(np.float64) - gpu.oracle_entries(p, bb, ii, jj))))
     assert err <= tolerance(p)
+
+
+def test_seeded_random_shapes_through_every_launch_form(gpu):
+    """Forty seeded 16-bit problems (ragged M and N, K any multiple of 8, four layouts, alpha and
+    beta drawn) through the selecting entry point with the hybrid form forced where it can run:
+    whatever mix of K cut, hybrid launch, split-K and plain launch a call resolves to, sampled
+    entries meet the bound."""
+    import paper_2003_06795_amd.binding as ks
+    r = np.random.default_rng(84)
+    ks.set_fast_path(True)
+    forms = set()
+    try:
+        for n in range(40):
+            M = int(r.integers(1, 700)) * 8
+            N = int(r.integers(1, 700)) * 8
+            K = int(r.integers(8, 400)) * 8
+            tA, tB = int(r.integers(0, 2)), int(r.integers(0, 2))
+            dtype = "bf16" if n % 4 else "f16"
+            p = wl.make_problem(dtype, tA, tB, M, N, K, alpha=float(r.uniform(-2, 2)),
+                                beta=float(r.choice([0.0, 1.0, -0.5])), seed=84, key=n, dist="normal")
+            dp = gpu.DeviceProblem(p)
+            ks.set_tail_split(8 if n % 2 else -1)
+            plan = plan_of(ks, gpu, p, dp, -1)
+            forms.add((plan["k_remainder"] > 0, plan["tail_split"] > 0, plan["split_k"] > 1, plan["path"]))
+            got = dp.run()
+            bb, ii, jj = gpu.sample_entries(p, 1500, n, tile=64)
+            err = float(np.max(np.abs(got[ii * p.ldc + jj].astype(np.float64) - gpu.oracle_entries(p, bb, ii, jj))))
+            assert err <= tolerance(p), (n, (tA, tB, M, N, K), plan, err)
+    finally:
+        ks.set_tail_split(-1)
+    assert len(forms) >= 4, forms
