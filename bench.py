@@ -370,6 +370,40 @@ def selector_live(ks, torch, n_shapes=6):
                 selected_over_best_geomean=geomean(ratios), worst=min(detail, key=lambda d: d["ratio"]))
 
 
+def bf16_launch_forms(ks, torch):
+    """The launch forms the named cells never take (their sizes are powers of two), each against the
+    form it replaces, on the selected kernel: a partly filled last round of tiles cut along K
+    (ks_set_tail_split) and a K that is not a whole number of K-steps (ks_set_fast_path)."""
+    out = []
+    for (M, N, K, tA, tB, what) in ((4352, 4352, 8192, 0, 1, "hybrid"), (4160, 4160, 4096, 0, 1, "hybrid"),
+                                    (4096, 4096, 4104, 0, 0, "cut_k"), (1024, 1024, 1032, 1, 0, "cut_k")):
+        s = 1.0 / np.sqrt(K)
+        A = (torch.randn(M * K, device="cuda") * s).to(torch.bfloat16)
+        B = (torch.randn(K * N, device="cuda") * s).to(torch.bfloat16)
+        C = torch.zeros(M * N, device="cuda")
+        args = (tA, tB, M, N, K, 1.0, A, M if tA else K, B, K if tB else N, 0.0, C, N)
+        ws = ensure_workspace(ks, torch, 256 << 20)
+        t = {}
+        for on in (True, False):
+            if what == "hybrid":
+                ks.set_tail_split(-1 if on else 0)
+            else:
+                ks.set_fast_path(on)
+            plan = ks.gemm_plan(ks.BF16, -1, *args)
+            est = float(np.median(ks.time_gemm(ks.BF16, -1, *args, warmup=1, iters=3, reps=1)))
+            warm = int(min(64, max(2, np.ceil(30.0 / max(est, 1e-3)))))
+            t[on] = (float(np.median(ks.time_gemm(ks.BF16, -1, *args, warmup=warm, iters=8, reps=1))), plan)
+        ks.set_tail_split(-1)
+        ks.set_fast_path(True)
+        fl = 2.0 * M * N * K
+        out.append(dict(M=M, N=N, K=K, layout="NT"[tA] + "NT"[tB], form=what, kernel=t[True][1]["kernel_id"],
+                        tail_split=t[True][1]["tail_split"], k_remainder=t[True][1]["k_remainder"],
+                        ms=t[True][0], tflops=fl / (t[True][0] * 1e-3) / 1e12,
+                        ms_in_the_form_it_replaces=t[False][0], speedup=t[False][0] / t[True][0]))
+        del A, B, C, ws
+    return out
+
+
 def bf16_report(ks, torch):
     """Selected bf16 kernels on the large/skinny set: TFLOP/s, fraction of the bf16 matrix peak, and
     fraction of what a pure MFMA loop sustains on the same operand values in this run."""
@@ -386,7 +420,8 @@ def bf16_report(ks, torch):
         f16 = ks.kernel_info(ks.BF16, c["kernel"])["core_name"] == "mfma16"
         c["frac_of_sustained_mfma"] = c["tflops"] / (sustained16 if f16 else sustained)
     big = [c for c in cells if min(c["M"], c["N"]) >= 2048]
-    return dict(cells=cells, geomean_tflops=geomean([c["tflops"] for c in cells]),
+    return dict(cells=cells, other_launch_forms=bf16_launch_forms(ks, torch),
+                geomean_tflops=geomean([c["tflops"] for c in cells]),
                 best_frac_of_peak=max(c["frac_of_peak"] for c in big),
                 best_frac_of_sustained_mfma=max(c["frac_of_sustained_mfma"] for c in big),
                 mfma_sustained=dict(what="ks_mfma_sustained: 2048 work-groups x 8 waves of 32x32x16 bf16 MFMAs on "
