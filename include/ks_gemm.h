@@ -313,7 +313,8 @@ int ks_set_tiles_per_workgroup(int n);
 
 /* The members with a balanced persistent form (ks_kernel_info_t::balanced_per_cu > 0) launch
  * 256 * balanced_per_cu work-groups (the launch shape is the run-time axis of the Section II
- * kernel).  1 <= per_cu <= 8 forces another count per compute unit for testing and tuning, and
+ * kernel); a 512-thread member with two per compute unit launches 256 when the problem has at
+ * most 96 tiles.  1 <= per_cu <= 8 forces another count per compute unit for testing and tuning, and
  * makes those members take the form on every call whose scratch is there (or that divides no
  * tile); 0 restores the members' own count and the per-call choice.  ks_workspace_bytes_needed
  * follows the forced count.  Results stay within the stated bound but the summation order of

@@ -498,7 +498,11 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
         // of the divided tiles and the second kernel cost more than the balance gains).  A forced work-group count
         // (ks_set_balanced_groups) takes the form whenever it can run.  Its scratch must be there
         // unless no tile is divided; otherwise the plain member runs.
-        const int64_t groups = sk_groups(d);
+        // With few tiles every tile is divided among many work-groups; a 512-thread member then
+        // runs faster with one work-group per compute unit than with two (fewer raw accumulator
+        // tiles per output tile, and the whole unit for each share): measured 2-10 % up to 80
+        // tiles of 128x128, even from 110 to 224, 3-5 % the other way from 270 on.
+        const int64_t groups = g_skPerCU == 0 && d->sk == 2 && d->threads >= 512 && grid64 <= 96 ? 256 : sk_groups(d);
         const int64_t tail = grid64 % groups;
         const bool fits = tail == 0 || (wsp.ptr && wsp.bytes >= sk_workspace_bytes(d) && aligned(wsp.ptr, 16));
         const bool pays = g_skPerCU > 0 || (tail != 0 && grid64 < 4 * groups && K >= 1024 && tail * kTiles >= groups);
