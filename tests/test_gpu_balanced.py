@@ -220,3 +220,26 @@ def test_balanced_form_at_full_size(gpu, ks, tA, tB):
         assert not bool(torch.isnan(C).any()), "kernel %d left entries unwritten" % kid
         err = float(np.max(np.abs(C[flat].cpu().numpy().astype(np.float64) - ref)))
         assert err <= tolerance(p), "kernel %d: %.3e > %.3e" % (kid, err, tolerance(p))
+
+
+def test_few_tiles_take_one_work_group_per_compute_unit(gpu, ks):
+    """A 512-thread member with two work-groups per compute unit launches 256 of them for problems
+    of at most 96 tiles (12 x 8 tiles here) and its own 512 from 97 tiles on (13 x 8, where one
+    more row of A adds a tile row); both sides of the limit against the oracle on sampled entries."""
+    import torch
+    for kid in balanced_ids(ks):
+        ki = ks.kernel_info(ks.F32, kid)
+        if ki["balanced_per_cu"] != 2 or ki["threads"] < 512:
+            continue
+        gpu.ensure_workspace(ks.workspace_bytes_needed(ks.F32, kid, 13 * ki["bm"], 8 * ki["bn"], 1))
+        for M, groups in ((12 * ki["bm"], 256), (12 * ki["bm"] + 1, 512)):
+            N, K = 8 * ki["bn"] - 24, 1096
+            p = wl.make_problem("f32", 0, 1, M, N, K, alpha=1.0, beta=0.5, seed=36, key=M)
+            dp = gpu.DeviceProblem(p)
+            plan = plan_of(ks, gpu, dp, kid)
+            assert plan["balanced_groups"] == groups and plan["workgroups"] == groups, (kid, M, plan)
+            assert plan["divided_tiles"] == (-(-M // ki["bm"]) * 8) % groups
+            got = dp.run(kid)
+            bb, ii, jj = gpu.sample_entries(p, 2000, 36, tile=ki["bm"])
+            err = float(np.max(np.abs(got[ii * p.ldc + jj].astype(np.float64) - gpu.oracle_entries(p, bb, ii, jj))))
+            assert err <= tolerance(p), (kid, M, err)
