@@ -34,7 +34,7 @@
  *     stream, or ordered by the caller); ks_gemm_with_workspace takes the
  *     scratch per call and has no such limit.  ks_set_workspace,
  *     ks_set_fast_path, ks_set_tiles_per_workgroup, ks_set_balanced_groups,
- *     ks_set_tail_split and ks_set_selector are not thread-safe: they change process-wide settings
+ *     ks_set_tail_split, ks_set_split_partitions and ks_set_selector are not thread-safe: they change process-wide settings
  *     that the compute entry points read.  ks_time_gemm keeps its events per
  *     host thread.  The library acts on the calling thread's current HIP device
  *     and never changes it.
@@ -333,6 +333,16 @@ int ks_set_balanced_groups(int per_cu);
  * many partitions (testing and tuning).  Results stay within the stated bound (the summation order
  * of the partitioned tiles changes).  Not thread-safe. */
 int ks_set_tail_split(int partitions);
+
+/* Members whose K split is chosen per call (split_k == 0) take the partition count of a cost
+ * estimate in K-steps (work-groups per round, K-steps per partition, the reduction pass).
+ * 1 <= partitions <= 256 forces that many instead (1 = no split), lowered to K-steps / 2 where a
+ * partition would hold fewer than two K-steps and to what the workspace holds, for testing and
+ * tuning (the partition count is part of the launch shape, the run-time axis of the Section II
+ * kernel); 0 restores the estimate.  ks_workspace_bytes_needed does not follow a forced count.
+ * Results stay within the stated bound (the summation order changes with the count).  Not
+ * thread-safe. */
+int ks_set_split_partitions(int partitions);
 
 /* Measurement aid: copies `bytes` (a multiple of 16; both device pointers 16-byte aligned) with a
  * plain one-read-one-write kernel (ks::copy_kernel).  Hardware traffic counters collected over a

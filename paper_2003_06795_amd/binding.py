@@ -62,7 +62,7 @@ _GEMM = [_i, _i, _i64, _i64, _i64, _f, _p, _i64, _p, _i64, _f, _p, _i64, _i64, _
 EXPORTS = [
     "ks_gemm_f32", "ks_gemm_bf16", "ks_gemm_f32_with_kernel", "ks_gemm_bf16_with_kernel",
     "ks_gemm_f16", "ks_gemm_f16_with_kernel", "ks_gemm_bias", "ks_gemm_out_bf16", "ks_gemm_static_scratch", "ks_gemm_with_workspace", "ks_gemm_plan", "ks_time_gemm", "ks_calibration_copy", "ks_mfma_sustained", "ks_bf16_ablation", "ks_num_kernels", "ks_kernel_info", "ks_select", "ks_features",
-    "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_balanced_groups", "ks_set_tail_split", "ks_set_workspace", "ks_workspace_bytes_needed",
+    "ks_set_selector", "ks_get_selector", "ks_set_fast_path", "ks_set_tiles_per_workgroup", "ks_set_balanced_groups", "ks_set_tail_split", "ks_set_split_partitions", "ks_set_workspace", "ks_workspace_bytes_needed",
     "ks_tune_performance", "ks_tune_normalise", "ks_tune_prune_tree", "ks_tune_achievable", "ks_tune_fit_selector",
     "ks_tune_predict", "ks_tune_selector_score", "ks_tune_prune_top_n", "ks_tune_prune_kmeans", "ks_tune_prune_hdbscan",
     "ks_tune_pca_variance", "ks_status_string",
@@ -108,6 +108,7 @@ def lib():
     L.ks_set_tiles_per_workgroup.argtypes = [_i]
     L.ks_set_balanced_groups.argtypes = [_i]
     L.ks_set_tail_split.argtypes = [_i]
+    L.ks_set_split_partitions.argtypes = [_i]
     L.ks_set_workspace.argtypes = [_p, ctypes.c_size_t]
     L.ks_workspace_bytes_needed.argtypes = [_i, _i, _i64, _i64, _i64]
     L.ks_workspace_bytes_needed.restype = ctypes.c_size_t
@@ -355,6 +356,11 @@ def set_balanced_groups(per_cu):
 def set_tail_split(partitions):
     """-1: hybrid launches of the 16-bit per-call-split members chosen per call; 0: never; 2..16: forced."""
     _check(lib().ks_set_tail_split(int(partitions)), "ks_set_tail_split")
+
+
+def set_split_partitions(partitions):
+    """0: per-call split members take the library's estimate; 1..256: forced K partitions (1 = no split)."""
+    _check(lib().ks_set_split_partitions(int(partitions)), "ks_set_split_partitions")
 
 
 def set_workspace(buf, nbytes=None):

@@ -97,6 +97,7 @@ int g_forceGeneric = 0;
 int g_tilesPerWG = 0;        // 0: chosen per call (multi_tiles); n >= 1: forced
 int g_skPerCU = 0;           // 0: the member's own count of work-groups per compute unit; n >= 1: forced
 int g_tailSplit = -1;        // -1: chosen per call (tail_split); 0: never; n >= 2: forced where it can run
+int g_splitForced = 0;       // 0: per-call split members take auto_split's count; n >= 1: forced (at least two K-steps each)
 void *g_ws = nullptr;
 size_t g_wsBytes = 0;
 
@@ -104,7 +105,7 @@ size_t g_wsBytes = 0;
 // `slots` (256 compute units times the work-groups that fit one); a work-group costs its K-steps
 // plus a fixed prologue/epilogue, and splitting adds the reduction pass.  The cheapest count wins
 // (the smaller one on ties); never more than 64 (fp32) or 256 (16-bit), never more than fills one
-// round, and at least two K-steps per partition.
+// round (16-bit) or four (fp32), and at least two K-steps per partition.
 //   fp32 members: twelve waves per compute unit, cost in K-steps as measured on the tuning set.
 //   16-bit members: their LDS stages (up to 144 KB) limit a compute unit to one to four
 //   work-groups, and a partition's tile of partial sums (written, then read by the reduction
@@ -121,7 +122,12 @@ int64_t split_slots(const InstanceDesc *d, bool f32) {
 
 int64_t auto_split_max(const InstanceDesc *d, int64_t tiles, bool f32) {
     const int64_t slots = split_slots(d, f32);
-    const int64_t s = (slots + tiles - 1) / (tiles > 0 ? tiles : 1);
+    int64_t s = (slots + tiles - 1) / (tiles > 0 ? tiles : 1);
+    // fp32: up to four rounds of partitions.  A count that overfills one round can still end
+    // sooner, e.g. 152 tiles in 5 partitions are three rounds of a fifth of K where unsplit tiles
+    // are one round of all of it; the cost estimate below matched the measured order of the counts
+    // on every shape tried.
+    if (f32 && tiles > 0 && 4 * slots / tiles > s) s = 4 * slots / tiles;
     const int64_t cap = f32 ? 64 : 256;
     return s < 1 ? 1 : (s > cap ? cap : s);
 }
@@ -131,9 +137,13 @@ int64_t auto_split(const InstanceDesc *d, int64_t tiles, int64_t kTiles, bool f3
     const int64_t partial = f32 ? 0 : (4LL * d->bm * d->bn) / ((int64_t)(d->bm + d->bn) * d->bk);
     int64_t best = 1, bestCost = -1;
     const int64_t smax = auto_split_max(d, tiles, f32);
+    // kTiles counts the steps of the work-group.  The K groups of an LDS-staged member share the
+    // compute unit's matrix pipe, so one of its steps lasts as many K-steps as it has groups; the
+    // waves of a K-sliced member wait on memory side by side and a step lasts one.
+    const int64_t stepCost = d->core != KS_CORE_KSLICE && d->kw > 1 ? d->kw : 1;
     for (int64_t s = 1; s <= smax && (s == 1 || 2 * s <= kTiles); ++s) {
         const int64_t rounds = (tiles * s + slots - 1) / slots;
-        const int64_t cost = rounds * ((kTiles + s - 1) / s + 6 + (s > 1 ? partial : 0)) + (s > 1 ? 10 : 0);
+        const int64_t cost = rounds * (stepCost * ((kTiles + s - 1) / s) + 6 + (s > 1 ? partial : 0)) + (s > 1 ? 10 : 0);
         if (bestCost < 0 || cost < bestCost) { bestCost = cost; best = s; }
     }
     return best;
@@ -468,6 +478,7 @@ int run_ws(Workspace wsp, int dtype, int id, int transA, int transB, int64_t M, 
         // and no more than the registered workspace can hold (1 = the plain single-kernel form)
         const int64_t steps = (kTiles + d->kw - 1) / d->kw;
         int64_t s = auto_split(d, (int64_t)p.tilesM * p.tilesN * batch, steps, dtype == KS_F32);
+        if (g_splitForced > 0) s = g_splitForced > 1 && 2 * (int64_t)g_splitForced > steps ? (steps / 2 > 1 ? steps / 2 : 1) : g_splitForced;
         const size_t per = (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
         if (!wsp.ptr) s = 1;
         else if ((size_t)s * per > wsp.bytes) s = (int64_t)(wsp.bytes / per);
@@ -691,6 +702,12 @@ extern "C" int ks_set_balanced_groups(int per_cu) {
 extern "C" int ks_set_tail_split(int partitions) {
     if (partitions != -1 && partitions != 0 && (partitions < 2 || partitions > 16)) return KS_ERR_INVALID_ARG;
     g_tailSplit = partitions;
+    return KS_OK;
+}
+
+extern "C" int ks_set_split_partitions(int partitions) {
+    if (partitions < 0 || partitions > 256) return KS_ERR_INVALID_ARG;
+    g_splitForced = partitions;
     return KS_OK;
 }
 
