@@ -302,6 +302,59 @@ def test_per_call_split_k_instances_with_and_without_workspace(gpu, dtype):
             check(p, single, ref, "%s kernel %d without workspace" % (dtype, kid))
 
 
+def plan_split(ks, gpu, dp, kid):
+    p = dp.p
+    return ks.gemm_plan(gpu.DT[p.dtype], kid, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb,
+                        p.beta, dp.C0, p.ldc, p.batch, p.strideA, p.strideB, p.strideC)["split_k"]
+
+
+def test_forced_partition_counts_and_more_than_one_round_of_partitions(gpu):
+    """ks_set_split_partitions forces the K partition count of the per-call split members (lowered
+    to K-steps / 2 where a partition would hold fewer than two K-steps); every forced count meets
+    the bound.  Left to itself an fp32 member may take more partitions than fill one round of
+    work-groups: 152 tiles of 64 x 64 with K = 2592 are cut three ways or more."""
+    import paper_2003_06795_amd.binding as ks
+    auto = [k for k in ids_of(gpu, "f32") if ks.kernel_info(ks.F32, k)["split_k"] == 0]
+    p = wl.make_problem("f32", 0, 1, 200, 136, 1000, alpha=-1.5, beta=0.5, seed=19)
+    dp, ref = gpu.DeviceProblem(p), gpu.oracle_full(p)
+    gpu.ensure_workspace(64 * p.M * p.N * 4)
+    try:
+        for kid in auto:
+            ki = ks.kernel_info(ks.F32, kid)
+            steps = -(-(-(-p.K // ki["bk"])) // ki["k_waves"])
+            for forced in (1, 2, 3, 7, 64):
+                ks.set_split_partitions(forced)
+                want = forced if forced == 1 or 2 * forced <= steps else max(steps // 2, 1)
+                assert plan_split(ks, gpu, dp, kid) == want, (kid, forced, steps)
+                check(p, dp.run(kid), ref, "f32 kernel %d, %d partitions forced" % (kid, forced))
+        ks.set_split_partitions(0)
+        with pytest.raises(Exception):
+            ks.set_split_partitions(257)
+        with pytest.raises(Exception):
+            ks.set_split_partitions(-1)
+        # bf16 members follow the forced count too
+        q = wl.make_problem("bf16", 0, 0, 264, 136, 2048, alpha=1.0, beta=0.0, seed=19, key=1, dist="normal")
+        dq, refq = gpu.DeviceProblem(q), gpu.oracle_full(q)
+        kid16 = [k for k in ids_of(gpu, "bf16") if ks.kernel_info(ks.BF16, k)["split_k"] == 0][0]
+        ks.set_split_partitions(5)
+        assert plan_split(ks, gpu, dq, kid16) == 5
+        check(q, dq.run(kid16), refq, "bf16 kernel %d, 5 partitions forced" % kid16)
+    finally:
+        ks.set_split_partitions(0)
+    wide = [k for k in auto if ks.kernel_info(ks.F32, k)["bm"] == 64 and ks.kernel_info(ks.F32, k)["bn"] == 64 and
+            ks.kernel_info(ks.F32, k)["threads"] == 512]
+    assert wide, "the 64x64 member with two K groups chooses its split per call"
+    r = wl.make_problem("f32", 0, 0, 1184, 480, 2592, seed=19, key=2)
+    dr = gpu.DeviceProblem(r)
+    gpu.ensure_workspace(ks.workspace_bytes_needed(ks.F32, wide[0], r.M, r.N, 1))
+    s = plan_split(ks, gpu, dr, wide[0])
+    assert s >= 3 and 152 * s > 256, s
+    got = dr.run(wide[0])
+    bb, ii, jj = gpu.sample_entries(r, 2000, 19, tile=64)
+    err = float(np.max(np.abs(got[ii * r.ldc + jj].astype(np.float64) - gpu.oracle_entries(r, bb, ii, jj))))
+    assert err <= tolerance(r), err
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_seeded_random_small_problems_every_kernel(gpu, dtype):
     """Brute force on tiny inputs: random sizes in [1, 70] (smaller than most tiles, so every edge
