@@ -63,6 +63,13 @@ def rows_of(config, limit=None, seed=0):
             for (tA, tB) in wl.CONFIG5_LAYOUTS:
                 out.append((i, "bf16", tA, tB, M, N, K, 1, 1.0, 0.0))
                 i += 1
+    elif config == 9:
+        # the bf16 tuning shapes (config 6) with A stored K x M: layouts TN and TT
+        i = 0
+        for (M, N, K) in wl.bf16_tuning_shapes():
+            for (tA, tB) in ((1, 0), (1, 1)):
+                out.append((i, "bf16", tA, tB, M, N, K, 1, 1.0, 0.0))
+                i += 1
     elif config == 7:
         for i, (s, tA, tB, M, N, K, b) in enumerate(wl.config2_extra_rows()):
             out.append((i, "f32", tA, tB, M, N, K, b, 1.0, 0.0))
