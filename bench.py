@@ -404,6 +404,49 @@ def bf16_launch_forms(ks, torch):
     return out
 
 
+def f32_launch_forms(ks, torch):
+    """The launch shape as the run-time axis on the fp32 side, each form against the one it replaces
+    on the kernel the deployed tree selects: the balanced persistent form against the plain launch of
+    the same member (ks_set_workspace: without scratch the member runs plain), and the K partition
+    count the library's estimate takes against no partitioning (ks_set_split_partitions)."""
+    out = []
+    for (M, N, K, tA, tB) in ((3016, 1448, 3656, 0, 0), (2200, 2432, 2400, 0, 1), (1184, 480, 2592, 0, 0),
+                              (96, 3016, 3392, 1, 0), (768, 768, 3072, 0, 1)):
+        A = torch.rand(M * K, device="cuda") * 2 - 1
+        B = torch.rand(K * N, device="cuda") * 2 - 1
+        C = torch.zeros(M * N, device="cuda")
+        args = (tA, tB, M, N, K, 1.0, A, M if tA else K, B, K if tB else N, 0.0, C, N)
+        ensure_workspace(ks, torch, 256 << 20)
+        plan = ks.gemm_plan(ks.F32, -1, *args)
+        kid = plan["kernel_id"]
+        if plan["balanced_groups"] > 0:
+            what = "balanced"
+        elif plan["split_k"] > 1:
+            what = "split_k"
+        else:
+            continue
+
+        def timed():
+            est = float(np.median(ks.time_gemm(ks.F32, kid, *args, warmup=1, iters=3, reps=1)))
+            warm = int(min(64, max(2, np.ceil(30.0 / max(est, 1e-3)))))
+            return float(np.median(ks.time_gemm(ks.F32, kid, *args, warmup=warm, iters=8, reps=1)))
+        on = timed()
+        if what == "balanced":
+            ks.set_workspace(None)
+            off = timed()
+            ensure_workspace(ks, torch, 256 << 20)
+        else:
+            ks.set_split_partitions(1)
+            off = timed()
+            ks.set_split_partitions(0)
+        fl = 2.0 * M * N * K
+        out.append(dict(M=M, N=N, K=K, layout="NT"[tA] + "NT"[tB], form=what, kernel=kid, split_k=plan["split_k"],
+                        balanced_groups=plan["balanced_groups"], ms=on, tflops=fl / (on * 1e-3) / 1e12,
+                        ms_in_the_form_it_replaces=off, speedup=off / on))
+        del A, B, C
+    return out
+
+
 def bf16_report(ks, torch):
     """Selected bf16 kernels on the large/skinny set: TFLOP/s, fraction of the bf16 matrix peak, and
     fraction of what a pure MFMA loop sustains on the same operand values in this run."""
@@ -601,6 +644,7 @@ def main():
         for c in large:
             c["frac_of_sustained_mfma"] = c["tflops"] / s32
         out["fp32_large"] = dict(cells=large, best_frac_of_peak=max(c["frac_of_peak"] for c in large),
+                                 other_launch_forms=f32_launch_forms(ks, torch),
                                  mfma_sustained=dict(tflops=s32, shader_mhz=mhz32,
                                                      what="32x32x2 fp32 MFMAs on U[-1,1) register operands"))
         for name in ("cfg3_sample", "cfg4"):
