@@ -266,3 +266,36 @@ def test_other_entry_points_at_full_size(gpu):
         # one bf16 step (2^-7 relative) on top of the accumulation bound
         assert np.all(np.abs(got - want) <= tolerance(p) + 2.0 ** -7 * np.abs(want))
         assert np.mean(got16 == want16) > 0.97
+
+
+def test_seeded_random_fp32_problems_through_whatever_form_the_call_resolves_to(gpu):
+    """Forty seeded fp32 problems of the tuning set's size range (dimensions log-uniform in 16 ..
+    4096, every fourth one in 1024 .. 4096, multiples of 8 or not, four layouts, alpha and beta drawn) through the selecting entry
+    point with a workspace registered: plain launches, several rounds of K partitions, the balanced
+    persistent form and three-dimensional grids all occur, and sampled entries (every edge tile
+    among them) meet the bound whichever the call resolves to."""
+    import paper_2003_06795_amd.binding as ks
+    r = np.random.default_rng(91)
+    gpu.ensure_workspace(256 << 20)
+    forms = set()
+    for n in range(40):
+        lo = 1024 if n % 4 == 3 else 16                                   # every fourth one in the mid-size band
+        M, N, K = (int(np.exp(r.uniform(np.log(lo), np.log(4096)))) for _ in range(3))
+        if n % 3:
+            M, N, K = (max(8, v // 8 * 8) for v in (M, N, K))
+        tA, tB = int(r.integers(0, 2)), int(r.integers(0, 2))
+        p = wl.make_problem("f32", tA, tB, M, N, K, alpha=float(r.uniform(-2, 2)), beta=float(r.choice([0.0, 1.0, -0.5])),
+                            seed=91, key=n)
+        dp = gpu.DeviceProblem(p)
+        plan = ks.gemm_plan(ks.F32, -1, p.transA, p.transB, p.M, p.N, p.K, p.alpha, dp.A, p.lda, dp.B, p.ldb, p.beta,
+                            dp.C0, p.ldc, p.batch, p.strideA, p.strideB, p.strideC)
+        ki = ks.kernel_info(ks.F32, plan["kernel_id"])
+        tiles = -(-M // ki["bm"]) * -(-N // ki["bn"])
+        slots = 256 * max(12 // (ki["threads"] // 64), 1)
+        forms.add(("balanced" if plan["balanced_groups"] else "rounds" if plan["split_k"] > 1 and
+                   tiles * plan["split_k"] > slots else "split" if plan["split_k"] > 1 else "plain", plan["grid_3d"]))
+        got = dp.run()
+        bb, ii, jj = gpu.sample_entries(p, 1500, n, tile=64)
+        err = float(np.max(np.abs(got[ii * p.ldc + jj].astype(np.float64) - gpu.oracle_entries(p, bb, ii, jj))))
+        assert err <= tolerance(p), (n, (tA, tB, M, N, K), plan, err)
+    assert {f for f, _ in forms} == {"plain", "split", "rounds", "balanced"} and {g for _, g in forms} == {0, 1}, forms
